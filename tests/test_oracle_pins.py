@@ -1,0 +1,446 @@
+"""Pins for the CPU oracle: each check ties an oracle function to something other than itself.
+
+What the paper fixes: Table 1 / Eq. 1 / Eq. 2 (window count and sizes), the worked example of
+Sec. 4.1 (horizon 3), windows are exact slices, index-batching feeds the same snapshots as the
+standard preprocessing of Algorithm 1, shuffle-then-partition covers every start once.
+What mathematics fixes: correctly rounded binary32 arithmetic (checked with exact rationals),
+the published splitmix64 stream, argsort by a library routine, bf16 rounding by a library
+conversion, mean/std by numpy in fp64.
+"""
+import os
+from fractions import Fraction
+
+import numpy as np
+import pytest
+
+import oracle
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def _golden_rows(name):
+    with open(os.path.join(GOLDEN, name)) as fh:
+        return [ln.split() for ln in fh if ln.strip() and not ln.startswith("#")]
+
+
+# ----------------------------------------------------------------------------------------------
+# exact-arithmetic helper (independent of the oracle): round a rational to binary32, RNE
+# ----------------------------------------------------------------------------------------------
+def round_to_f32(q: Fraction) -> np.float32:
+    if q == 0:
+        return np.float32(0.0)
+    sign = -1 if q < 0 else 1
+    a = abs(q)
+    # find e with 2^e <= a < 2^(e+1)
+    e = a.numerator.bit_length() - a.denominator.bit_length()
+    if Fraction(2) ** e > a:
+        e -= 1
+    if Fraction(2) ** (e + 1) <= a:
+        e += 1
+    e = max(e, -126)  # subnormals share the exponent of the smallest normal
+    ulp = Fraction(2) ** (e - 23)
+    m = a / ulp  # mantissa in units of ulp
+    lo = m.numerator // m.denominator
+    rem = m - lo
+    if rem > Fraction(1, 2) or (rem == Fraction(1, 2) and (lo & 1)):
+        lo += 1
+    val = Fraction(lo) * ulp
+    if val >= Fraction(2) ** 128:
+        return np.float32(sign * np.inf)
+    return np.float32(sign * float(val))  # exactly representable, float() is exact here
+
+
+def exact_standardize(v, mu, sigma) -> np.float32:
+    d = round_to_f32(Fraction(float(v)) - Fraction(float(mu)))
+    return round_to_f32(Fraction(float(d)) / Fraction(float(sigma)))
+
+
+def test_round_helper_matches_numpy_cast():
+    rng = np.random.default_rng(1)
+    for v in rng.standard_normal(200) * 10.0 ** rng.integers(-30, 30, 200):
+        assert round_to_f32(Fraction(float(v))) == np.float32(v)
+
+
+# ----------------------------------------------------------------------------------------------
+# counting: Eq. 1, Eq. 2, Table 1
+# ----------------------------------------------------------------------------------------------
+def test_table1_sizes_follow_eq1():
+    # Eq. 1 in float64 bytes reproduces every printed "size after preprocessing" to the printed
+    # digits; this fixes the window count as entries - (2*horizon - 1), not entries - 2*horizon - 1
+    # as one sentence of Sec. 4.1 could be read.
+    rows = _golden_rows("table1_sizes.txt")
+    assert len(rows) == 5
+    for name, nodes, entries, feats, horizon, printed, unit in rows:
+        elems = oracle.eq1_materialized_elements(int(entries), int(horizon), int(nodes), int(feats))
+        size = elems * 8 / (2 ** 30 if unit == "GiB" else 10 ** 6)
+        assert f"{size:.2f}" == f"{float(printed):.2f}", (name, size, printed)
+        # the misreading (entries - 2*horizon - 1 windows) must not also fit
+        wrong = 2 * (int(entries) - 2 * int(horizon) - 1) * int(horizon) * int(nodes) * int(feats)
+        assert wrong != elems
+
+
+def test_window_count_is_entries_minus_2h_minus_1():
+    for T, h in [(34272, 12), (52116, 12), (105120, 12), (2000, 12), (6, 3)]:
+        assert oracle.window_count(T, h, h) == T - (2 * h - 1)
+    # the five benchmark workloads
+    assert oracle.window_count(2000, 12, 12) == 1977
+    assert oracle.window_count(34272, 12, 12) == 34249
+    assert oracle.window_count(52116, 12, 12) == 52093
+    assert oracle.window_count(105120, 12, 12) == 105097
+    # separate input/target lengths, degenerate series
+    assert oracle.window_count(40, 5, 3) == 33
+    assert oracle.window_count(24, 12, 12) == 1
+    assert oracle.window_count(23, 12, 12) == 0
+    assert oracle.window_count(0, 12, 12) == 0
+
+
+def test_eq2_index_batching_size():
+    # Eq. 2: one copy of the data plus one index per window.
+    e, h, n, f = 105120, 12, 11160, 2
+    assert oracle.eq2_index_batching_elements(e, h, n, f) == e * n * f + oracle.window_count(e, h, h)
+    # the growth factor of Eq. 1 over the raw data approaches 2*horizon
+    ratio = oracle.eq1_materialized_elements(e, h, n, f) / (e * n * f)
+    assert 2 * h * 0.999 < ratio < 2 * h
+
+
+def test_epoch_moves_what_standard_method_stores():
+    # One fp32 epoch reads+writes (P+Q)*R*(4+4) bytes per snapshot: numerically Eq. 1 in float64.
+    T, N, F, h = 34272, 207, 2, 12
+    per_snapshot = (h + h) * N * F * (4 + 4)
+    assert oracle.window_count(T, h, h) * per_snapshot == oracle.eq1_materialized_elements(T, h, N, F) * 8
+
+
+# ----------------------------------------------------------------------------------------------
+# windows are slices: worked example, numpy slicing, sliding_window_view, Algorithm 1
+# ----------------------------------------------------------------------------------------------
+def _graph_id_series(T, N=1, F=1):
+    # data[t] carries its own graph ID t in every element
+    return np.ascontiguousarray(np.broadcast_to(np.arange(T, dtype=np.float32)[:, None, None], (T, N, F)))
+
+
+def test_sec41_worked_example_horizon3():
+    (h, start, xs, ys), = _golden_rows("fig3_example.txt")
+    h, start = int(h), int(start)
+    data = _graph_id_series(8)
+    x, y = oracle.build_batch(data, oracle.F32, h, h, [0.0], [1.0], [start])
+    assert x[0, :, 0, 0].tolist() == [float(v) for v in xs.split(",")]
+    assert y[0, :, 0, 0].tolist() == [float(v) for v in ys.split(",")]
+
+
+def test_windows_are_exact_numpy_slices():
+    rng = np.random.default_rng(2)
+    T, N, F, P, Q = 50, 7, 3, 5, 4
+    data = rng.standard_normal((T, N, F)).astype(np.float32)
+    starts = np.array([0, 41, 17, 17, 3], dtype=np.int32)  # 41 = last valid start, repeats allowed
+    zero, one = np.zeros(F, np.float32), np.ones(F, np.float32)
+    x, y = oracle.build_batch(data, oracle.F32, P, Q, zero, one, starts)
+    for j, s in enumerate(starts):
+        assert np.array_equal(x[j].view(np.uint32), data[s:s + P].view(np.uint32))
+        assert np.array_equal(y[j].view(np.uint32), data[s + P:s + P + Q].view(np.uint32))
+
+
+def test_windows_match_sliding_window_view():
+    rng = np.random.default_rng(3)
+    T, N, F, P, Q = 40, 3, 2, 6, 2
+    data = rng.standard_normal((T, N, F)).astype(np.float32)
+    n = oracle.window_count(T, P, Q)
+    zero, one = np.zeros(F, np.float32), np.ones(F, np.float32)
+    x, y = oracle.build_batch(data, oracle.F32, P, Q, zero, one, np.arange(n, dtype=np.int32))
+    sx = np.lib.stride_tricks.sliding_window_view(data, P, axis=0)  # [T-P+1, N, F, P]
+    sy = np.lib.stride_tricks.sliding_window_view(data, Q, axis=0)
+    assert np.array_equal(x, np.moveaxis(sx, -1, 1)[:n])
+    assert np.array_equal(y, np.moveaxis(sy, -1, 1)[P:P + n])
+
+
+@pytest.mark.parametrize("T,N,F,P,Q", [(24, 1, 1, 12, 12), (25, 3, 2, 12, 12), (40, 3, 2, 5, 3),
+                                       (40, 1, 2, 3, 7), (30, 2, 3, 1, 1)])
+def test_index_batching_equals_algorithm1(T, N, F, P, Q):
+    # Sec. 5.1: index-batching feeds the same snapshots as standard batching.  Algorithm 1
+    # materialises everything; indexing its stacks by any order of starts must give the batches.
+    rng = np.random.default_rng(T * 100 + N)
+    data = (rng.standard_normal((T, N, F)) * 20 + 50).astype(np.float32)
+    mean = rng.standard_normal(F).astype(np.float32)
+    std = (rng.random(F) + 0.5).astype(np.float32)
+    x_all, y_all = oracle.alg1_preprocess(data, P, Q, mean, std)
+    n = oracle.window_count(T, P, Q)
+    assert x_all.shape == (n, P, N, F) and y_all.shape == (n, Q, N, F)
+    order = rng.permutation(n).astype(np.int32)
+    x, y = oracle.build_batch(data, oracle.F32, P, Q, mean, std, order)
+    assert np.array_equal(x.view(np.uint32), x_all[order].view(np.uint32))
+    assert np.array_equal(y.view(np.uint32), y_all[order].view(np.uint32))
+    # y is the slice one input length ahead of x: where they overlap in time they hold equal values
+    if n > P:
+        assert np.array_equal(y_all[0, 0], x_all[P, 0])
+
+
+def test_alg1_against_plain_numpy_loop():
+    # Algorithm 1 written the way its listing reads, with numpy doing the arithmetic in fp32.
+    rng = np.random.default_rng(5)
+    T, N, F, h = 30, 4, 2, 4
+    data = (rng.standard_normal((T, N, F)) * 9 + 60).astype(np.float32)
+    mean = np.array([59.5, 0.25], np.float32)
+    std = np.array([9.25, 0.75], np.float32)
+    xs, ys = [], []
+    for w in range(T - (2 * h - 1)):
+        xs.append(data[w:w + h])
+        ys.append(data[w + h:w + 2 * h])
+    xs, ys = np.stack(xs, axis=0), np.stack(ys, axis=0)
+    xs, ys = (xs - mean) / std, (ys - mean) / std  # numpy fp32: one rounding per operation
+    x_all, y_all = oracle.alg1_preprocess(data, h, h, mean, std)
+    assert xs.dtype == np.float32
+    assert np.array_equal(x_all.view(np.uint32), xs.view(np.uint32))
+    assert np.array_equal(y_all.view(np.uint32), ys.view(np.uint32))
+
+
+def test_start_out_of_range_is_rejected():
+    data = _graph_id_series(30)
+    with pytest.raises(ValueError):
+        oracle.build_batch(data, oracle.F32, 12, 12, [0.0], [1.0], [7])  # n = 7, valid 0..6
+    with pytest.raises(ValueError):
+        oracle.build_batch(data, oracle.F32, 12, 12, [0.0], [1.0], [-1])
+    oracle.build_batch(data, oracle.F32, 12, 12, [0.0], [1.0], [6])
+
+
+# ----------------------------------------------------------------------------------------------
+# standardise: two correctly rounded binary32 operations
+# ----------------------------------------------------------------------------------------------
+def test_standardize_closed_forms():
+    assert oracle.standardize(5.0, 1.0, 2.0) == 2.0
+    assert oracle.standardize(1.0, 5.0, 2.0) == -2.0  # sign of the subtraction
+    assert oracle.standardize(7.0, 1.0, 3.0) == float(np.float32(2.0))
+    assert oracle.standardize(1.0, 0.0, 3.0) == float(np.float32(1.0) / np.float32(3.0))
+    v = float(np.float32(0.1234567))
+    assert oracle.standardize(v, 0.0, 1.0) == v  # identity channel is bit exact
+
+
+def test_standardize_is_correctly_rounded_twice():
+    rng = np.random.default_rng(7)
+    n_diff_recip = n_diff_single = 0
+    for _ in range(4000):
+        v = np.float32(rng.uniform(0, 80))
+        mu = np.float32(rng.uniform(40, 70))
+        sigma = np.float32(rng.uniform(0.5, 20))
+        want = exact_standardize(v, mu, sigma)
+        got = np.float32(oracle.standardize(float(v), float(mu), float(sigma)))
+        assert got.view(np.uint32) == want.view(np.uint32), (v, mu, sigma)
+        # the shortcuts the method must NOT take really are different functions:
+        recip = np.float32(np.float32(v - mu) * (np.float32(1.0) / sigma))
+        single = round_to_f32((Fraction(float(v)) - Fraction(float(mu))) / Fraction(float(sigma)))
+        n_diff_recip += int(recip.view(np.uint32) != want.view(np.uint32))
+        n_diff_single += int(single.view(np.uint32) != want.view(np.uint32))
+    assert n_diff_recip > 0 and n_diff_single > 0  # so the check above can tell them apart
+
+
+def test_standardize_special_values():
+    inf, nan = float("inf"), float("nan")
+    assert oracle.standardize(inf, 1.0, 2.0) == inf
+    assert oracle.standardize(-inf, 1.0, 2.0) == -inf
+    assert np.isnan(oracle.standardize(nan, 1.0, 2.0))
+    tiny = float(np.float32(1e-45))  # smallest subnormal survives an identity standardise
+    assert oracle.standardize(tiny, 0.0, 1.0) == tiny
+    sub = exact_standardize(np.float32(3e-38), np.float32(0.0), np.float32(7.0))  # subnormal result
+    assert np.float32(oracle.standardize(float(np.float32(3e-38)), 0.0, 7.0)).view(np.uint32) == sub.view(np.uint32)
+    assert sub != 0 and abs(float(sub)) < 1.1754944e-38
+
+
+def test_standardised_output_has_zero_mean_unit_std():
+    rng = np.random.default_rng(11)
+    T, N, F = 300, 20, 2
+    data = np.empty((T, N, F), np.float32)
+    data[..., 0] = rng.normal(60, 9, (T, N))
+    data[..., 1] = rng.random((T, N))
+    mean, std = oracle.series_stats(data)
+    # a single sample covering the whole series: P = T-1, Q = 1
+    x, y = oracle.build_batch(data, oracle.F32, T - 1, 1, mean, std, [0])
+    whole = np.concatenate([x[0], y[0]], axis=0).astype(np.float64)
+    for f in range(F):
+        assert abs(whole[..., f].mean()) < 1e-5
+        assert abs(whole[..., f].std() - 1.0) < 1e-5
+    # and feature f uses mean[f]/std[f], not the other feature's
+    assert abs(float(mean[0]) - 60) < 1 and abs(float(mean[1]) - 0.5) < 0.05
+
+
+def test_series_stats_against_numpy():
+    rng = np.random.default_rng(13)
+    data = (rng.normal(55, 12, (500, 33, 2))).astype(np.float32)
+    data[rng.random(data.shape) < 0.01] = 0.0
+    mean, std = oracle.series_stats(data)
+    d64 = data.astype(np.float64)
+    for f in range(2):
+        assert mean[f] == np.float32(d64[..., f].mean()) or abs(float(mean[f]) - d64[..., f].mean()) < 1e-6
+        assert abs(float(std[f]) - d64[..., f].std(ddof=0)) < 1e-5
+        assert abs(float(std[f]) - d64[..., f].std(ddof=1)) > abs(float(std[f]) - d64[..., f].std(ddof=0)) - 1e-9
+    # exact case: integers
+    small = np.arange(24, dtype=np.float32).reshape(4, 3, 2)
+    m, s = oracle.series_stats(small)
+    assert m.tolist() == [11.0, 12.0]
+    assert np.allclose(s, [np.sqrt(np.mean((np.arange(0, 24, 2) - 11.0) ** 2))] * 2, rtol=1e-7)
+
+
+def test_alg1_train_stats_definition():
+    # Algorithm 1: scalar mean/std over the first round(0.7*n) windows of the stacked x.
+    rng = np.random.default_rng(17)
+    T, N, F, h = 60, 3, 2, 4
+    data = rng.normal(50, 10, (T, N, F)).astype(np.float32)
+    n = T - (2 * h - 1)
+    x = np.stack([data[w:w + h] for w in range(n)], axis=0)
+    x_train = x[:round(n * 0.70)].astype(np.float64)
+    mean, std = oracle.alg1_train_stats(data, h, h)
+    assert abs(mean - x_train.mean()) < 1e-9
+    assert abs(std - x_train.std()) < 1e-9
+
+
+# ----------------------------------------------------------------------------------------------
+# epoch order: key mixer, sort, partition
+# ----------------------------------------------------------------------------------------------
+def test_mix64_published_stream():
+    want = [int(r[0], 16) for r in _golden_rows("splitmix64_state0.txt")]
+    assert oracle.splitmix64_stream(0, 3) == want
+    g = 0x9E3779B97F4A7C15
+    assert oracle.mix64(g) == want[0]
+    assert oracle.mix64((2 * g) & (2 ** 64 - 1)) == want[1]
+
+
+def test_key_depends_on_every_argument_and_is_chained_mixing():
+    g, mask = 0x9E3779B97F4A7C15, 2 ** 64 - 1
+    for seed, epoch, i in [(0, 0, 0), (7, 2, 12345), (2 ** 64 - 1, 2 ** 63, 105096)]:
+        h0 = oracle.mix64((seed + g) & mask)
+        h1 = oracle.mix64(((h0 ^ epoch) + g) & mask)
+        assert oracle.key(seed, epoch, i) == oracle.mix64(((h1 ^ i) + g) & mask)
+    base = oracle.key(3, 4, 5)
+    assert len({base, oracle.key(4, 4, 5), oracle.key(3, 5, 5), oracle.key(3, 4, 6),
+                oracle.key(4, 3, 5), oracle.key(5, 4, 3)}) == 6  # arguments are not interchangeable
+
+
+def test_key_bits_look_uniform():
+    keys = np.array([oracle.key(0, 0, i) for i in range(4096)], dtype=np.uint64)
+    assert len(np.unique(keys)) == 4096
+    for bit in (0, 7, 31, 32, 63):
+        frac = float(((keys >> np.uint64(bit)) & np.uint64(1)).mean())
+        assert 0.45 < frac < 0.55
+
+
+@pytest.mark.parametrize("seed,epoch,n", [(0, 0, 1977), (7, 1, 6569), (123, 9, 1), (5, 5, 2)])
+def test_epoch_perm_is_argsort_of_keys(seed, epoch, n):
+    perm = oracle.epoch_perm(seed, epoch, n)
+    keys = np.array([oracle.key(seed, epoch, i) for i in range(n)], dtype=np.uint64)
+    assert np.array_equal(np.sort(perm), np.arange(n))  # a permutation: every start exactly once
+    assert np.all(keys[perm][1:] >= keys[perm][:-1])  # keys ascend along the order
+    assert np.array_equal(perm, np.lexsort((np.arange(n), keys)))  # library argsort by (key, index)
+    assert np.array_equal(perm, np.argsort(keys, kind="stable"))
+
+
+def test_key_chain_regression_vectors():
+    # Stored values written from the oracle by tests/golden/make_key_vectors.py; they guard the
+    # oracle against silent edits (the choice itself is this build's reading of Sec. 4.2).
+    for row in _golden_rows("key_chain_vectors.txt"):
+        if row[0] == "key":
+            assert oracle.key(int(row[1]), int(row[2]), int(row[3])) == int(row[4], 16)
+        else:
+            want = [int(v) for v in row[4].split(",")]
+            assert oracle.epoch_perm(int(row[1]), int(row[2]), int(row[3])).tolist() == want
+
+
+def test_sort_breaks_ties_by_lower_index():
+    rng = np.random.default_rng(19)
+    keys = rng.integers(0, 16, 5000).astype(np.uint64)  # only 16 distinct keys: ties everywhere
+    perm = oracle.sort_pairs(keys)
+    assert np.array_equal(perm, np.argsort(keys, kind="stable"))
+    for k in range(16):
+        idx = perm[keys[perm] == k]
+        assert np.all(np.diff(idx) > 0)
+    big = np.array([2 ** 63, 1, 2 ** 64 - 1, 0, 2 ** 63], dtype=np.uint64)  # unsigned compare
+    assert oracle.sort_pairs(big).tolist() == [3, 1, 0, 4, 2]
+
+
+def test_epochs_and_seeds_give_different_orders():
+    n = 6569
+    perms = [oracle.epoch_perm(7, e, n) for e in range(3)] + [oracle.epoch_perm(8, 0, n)]
+    for a in range(len(perms)):
+        for b in range(a + 1, len(perms)):
+            assert np.mean(perms[a] == perms[b]) < 0.01
+    assert np.array_equal(perms[0], oracle.epoch_perm(7, 0, n))  # reproducible
+
+
+def test_partition_covers_every_start_once():
+    n, world = 105097, 16
+    perm = oracle.epoch_perm(7, 0, n)
+    pieces, sizes = [], []
+    prev_hi = 0
+    for r in range(world):
+        lo, hi = oracle.rank_share(n, r, world)
+        assert lo == prev_hi  # contiguous, in rank order
+        prev_hi = hi
+        share = oracle.epoch_indices(7, 0, r, world, n)
+        assert np.array_equal(share, perm[lo:hi])
+        pieces.append(share)
+        sizes.append(hi - lo)
+    assert prev_hi == n
+    assert max(sizes) - min(sizes) <= 1
+    assert np.array_equal(np.sort(np.concatenate(pieces)), np.arange(n))
+    assert oracle.rank_share(n, 3, 16) == (19705, 26274)  # the bf16 workload's rank
+    assert oracle.rank_share(10, 0, 1) == (0, 10)
+    assert [oracle.rank_share(3, r, 5) for r in range(5)] == [(0, 0), (0, 1), (1, 1), (1, 2), (2, 3)]
+    with pytest.raises(ValueError):
+        oracle.rank_share(10, 4, 4)
+
+
+# ----------------------------------------------------------------------------------------------
+# bf16 storage
+# ----------------------------------------------------------------------------------------------
+def test_bf16_rounding_matches_library_conversion():
+    torch = pytest.importorskip("torch")
+    hi = np.arange(1 << 16, dtype=np.uint32) << 16
+    lows = np.array([0x0000, 0x0001, 0x7FFF, 0x8000, 0x8001, 0xFFFF, 0x4000, 0xC000], np.uint32)
+    bits = (hi[:, None] | lows[None, :]).ravel()
+    vals = bits.view(np.float32)
+    got = oracle.store_bf16(vals)
+    ref = torch.from_numpy(vals.copy()).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
+    finite_or_inf = ~np.isnan(vals)
+    assert np.array_equal(got[finite_or_inf], ref[finite_or_inf])
+    # NaN stays NaN, keeps its sign
+    g_nan = got[~finite_or_inf]
+    assert np.all((g_nan & 0x7F80) == 0x7F80) and np.all((g_nan & 0x007F) != 0)
+    assert np.array_equal(g_nan >> 15, (bits[~finite_or_inf] >> 31).astype(np.uint16))
+
+
+def test_bf16_ties_and_carries():
+    f = lambda b: np.array([b], np.uint32).view(np.float32)[0]
+    assert oracle.bf16_from_f32(f(0x3F808000)) == 0x3F80  # tie, even stays
+    assert oracle.bf16_from_f32(f(0x3F818000)) == 0x3F82  # tie, odd goes up
+    assert oracle.bf16_from_f32(f(0x3F808001)) == 0x3F81
+    assert oracle.bf16_from_f32(f(0x3FFFFFFF)) == 0x4000  # carry into the exponent
+    assert oracle.bf16_from_f32(f(0x7F7FFFFF)) == 0x7F80  # largest finite rounds to +Inf
+    assert oracle.bf16_from_f32(f(0x80000001)) == 0x8000  # tiny negative -> -0
+    w = oracle.widen_bf16(np.array([0x3F80, 0xC000, 0x0001], np.uint16))
+    assert w.view(np.uint32).tolist() == [0x3F800000, 0xC0000000, 0x00010000]
+
+
+def test_bf16_series_batch_uses_widened_values():
+    rng = np.random.default_rng(23)
+    T, N, F, P, Q = 30, 5, 2, 3, 2
+    data = rng.normal(60, 9, (T, N, F)).astype(np.float32)
+    stored = oracle.store_bf16(data)
+    widened = (stored.astype(np.uint32) << 16).view(np.float32)
+    assert np.max(np.abs(widened - data) / np.abs(data)) <= 2.0 ** -8
+    mean, std = np.array([60, 0.5], np.float32), np.array([9, 0.3], np.float32)
+    starts = np.array([4, 0, 25], np.int32)
+    xb, yb = oracle.build_batch(stored, oracle.BF16, P, Q, mean, std, starts)
+    xf, yf = oracle.build_batch(widened, oracle.F32, P, Q, mean, std, starts)
+    assert np.array_equal(xb.view(np.uint32), xf.view(np.uint32))
+    assert np.array_equal(yb.view(np.uint32), yf.view(np.uint32))
+
+
+def test_fused_equals_prestandardised_then_sliced():
+    # Sec. 4.1 slices "the standardized data"; this build standardises inside the gather.
+    # In fp32 the same two roundings happen per element either way.
+    rng = np.random.default_rng(29)
+    T, N, F, P, Q = 64, 9, 2, 12, 12
+    data = rng.normal(60, 9, (T, N, F)).astype(np.float32)
+    mean, std = oracle.series_stats(data)
+    pre = ((data - mean) / std).astype(np.float32)
+    starts = rng.permutation(oracle.window_count(T, P, Q)).astype(np.int32)[:16]
+    x, y = oracle.build_batch(data, oracle.F32, P, Q, mean, std, starts)
+    for j, s in enumerate(starts):
+        assert np.array_equal(x[j].view(np.uint32), pre[s:s + P].view(np.uint32))
+        assert np.array_equal(y[j].view(np.uint32), pre[s + P:s + P + Q].view(np.uint32))
