@@ -1,0 +1,136 @@
+/*
+ * pgti.h -- C ABI of the MI355X (gfx950) index-batching library.
+ *
+ * What it does (PGT-I, arXiv 2507.11683): instead of materialising every sliding-window
+ * snapshot of a spatiotemporal series (Algorithm 1; size given by Eq. 1) and copying batches
+ * host-to-device, ONE copy of the [T, N, F] series stays resident in HBM together with one
+ * start index per window (Eq. 2), and each training batch is rebuilt on the device from start
+ * indices (Sec. 4.1, "Index-Batching" and "GPU-Index-Batching").  Each epoch the starts are
+ * shuffled and split by worker (Sec. 4.2).
+ *
+ * Conventions
+ *   - Plain C linkage.  No exceptions or aborts cross the boundary.
+ *   - Every function that returns int returns >= 0 on success and a negative pgti_status on
+ *     failure; pgti_last_error() then describes it (thread-local string).
+ *   - "host" / "device" in a comment says where a pointer must live.
+ *   - The library owns the resident series, the statistics and the index buffers; the caller
+ *     owns every pointer it passes in (host inputs may be freed as soon as the call returns)
+ *     and the HIP stream.
+ *   - A context is bound to one GPU and is not thread-safe.  Contexts are independent.
+ *   - Layouts are row-major with the last index fastest: series [T, N, F];
+ *     x [B, P, N, F]; y [B, Q, N, F].
+ */
+#ifndef PGTI_H
+#define PGTI_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct pgti_ctx pgti_ctx; /* opaque */
+
+typedef enum {
+    PGTI_F32 = 0, /* series stored as IEEE binary32 */
+    PGTI_BF16 = 1 /* series stored as bfloat16 (fp32 rounded to nearest, ties to even) */
+} pgti_dtype;
+
+typedef enum {
+    PGTI_OK = 0,
+    PGTI_ERR_ARG = -1,   /* null pointer, non-positive size, misaligned output, bad enum */
+    PGTI_ERR_STATE = -2, /* call order: no series loaded / no epoch indices generated */
+    PGTI_ERR_RANGE = -3, /* batch_no beyond the share, rank >= world, T < P + Q, too many windows */
+    PGTI_ERR_STATS = -4, /* a standard deviation is zero or a statistic is not finite */
+    PGTI_ERR_OOM = -5,   /* device or pinned-host allocation failed */
+    PGTI_ERR_HIP = -6    /* any other HIP runtime error (text in pgti_last_error) */
+} pgti_status;
+
+/* Creates a context on GPU `device` (ordinal as seen by HIP).  *out receives the handle. */
+int pgti_create(pgti_ctx** out, int device);
+
+/* Frees everything the context owns after waiting for the device work it enqueued on its own
+ * stream.  The caller must have finished (or synchronised) its own streams first.  NULL is ok. */
+void pgti_destroy(pgti_ctx* c);
+
+/*
+ * Resident store (Sec. 4.1, GPU-Index-Batching: the data is moved to GPU memory once; index
+ * batching keeps a single copy of it, Eq. 2).
+ *
+ * Copies host_series (HOST, fp32, [T, N, F]) to HBM in `storage` precision and fixes the window
+ * geometry: P input steps, Q target steps (the paper's single `horizon` is P = Q), batch size B.
+ * The number of valid starts becomes n = T - (P + Q) + 1 (Eq. 1, Eq. 2).
+ * mean, std: HOST, F floats each: the per-feature statistics used by pgti_build_batch
+ * (Algorithm 1 standardises with (v - mu) / sigma).  If BOTH are NULL the library computes, on
+ * the device, the mean and the population standard deviation of every feature over all T*N
+ * values of the fp32 input.  Exactly one of them NULL is PGTI_ERR_ARG.
+ * Replaces any series loaded before; invalidates epoch indices.  Synchronous: on return the
+ * host buffers are no longer referenced.
+ * Errors: ARG, RANGE (T < P + Q, or n >= 2^31), STATS, OOM, HIP.
+ */
+int pgti_load_series(pgti_ctx* c, const float* host_series, int64_t T, int32_t N, int32_t F,
+                     int32_t P, int32_t Q, int32_t B, pgti_dtype storage, const float* mean,
+                     const float* std);
+
+/* Same as pgti_load_series but the fp32 source already lives in DEVICE memory (for a caller
+ * that produced or staged the series on the GPU).  The source is not modified or retained. */
+int pgti_load_series_device(pgti_ctx* c, const float* device_series, int64_t T, int32_t N,
+                            int32_t F, int32_t P, int32_t Q, int32_t B, pgti_dtype storage,
+                            const float* mean, const float* std);
+
+/* Reads back the statistics in use (HOST, F floats each; either may be NULL). */
+int pgti_get_stats(pgti_ctx* c, float* mean_out, float* std_out);
+
+/*
+ * Epoch index generation (Sec. 4.2: the dataset is shuffled at the start of each epoch, then
+ * partitioned according to the number of workers; every worker holds the full data, so the
+ * shuffle is global and needs no communication).
+ *
+ * The epoch order is the list of starts 0..n-1 sorted ascending by (key_i, i), where
+ * key_i = M((h1 ^ i) + g), h1 = M((h0 ^ epoch) + g), h0 = M(seed + g), M the splitmix64 output
+ * function and g = 0x9E3779B97F4A7C15; computed on the device with a stable least-significant-
+ * digit radix sort.  Rank `rank` of `world` owns order[lo, hi), lo = floor(rank*n/world),
+ * hi = floor((rank+1)*n/world): no padding, no dropping.  *n_share (HOST, may be NULL)
+ * receives hi - lo.  Same arguments give the same bits on every run.
+ * Replaces the previous share.  Stream ordering is handled inside: the sort waits for batch
+ * builds already enqueued through this context, and later batch builds wait for the sort.
+ * Does not block the host.
+ * Errors: STATE (no series), RANGE (rank >= world, world == 0), HIP.
+ */
+int pgti_epoch_indices(pgti_ctx* c, uint64_t seed, uint64_t epoch, uint32_t rank, uint32_t world,
+                       int64_t* n_share);
+
+/* Test hook: copies the current share to host_out (HOST, int32, room for `capacity` entries).
+ * Blocks until the sort has finished.  Returns the share length, or ERR_ARG if it does not fit. */
+int64_t pgti_get_indices(pgti_ctx* c, int32_t* host_out, int64_t capacity);
+
+/* Number of batches in the current share, ceil(n_share / B); STATE if there is none. */
+int64_t pgti_num_batches(pgti_ctx* c);
+
+/*
+ * Batch build = fused gather + standardise (Sec. 4.1: x = data[start : start+horizon],
+ * y = data[start+horizon : start+2*horizon], rebuilt at run time from the start index;
+ * Algorithm 1: (v - mu) / sigma).
+ *
+ * Batch `batch_no` holds the samples share[batch_no*B ... min((batch_no+1)*B, n_share)) in that
+ * order.  For sample j with start s:  out_x[j, p, :, f] = (S[s+p, :, f] - mean[f]) / std[f],
+ * p < P;  out_y[j, q, :, f] = (S[s+P+q, :, f] - mean[f]) / std[f], q < Q.  The subtraction and
+ * the division are two separately rounded IEEE binary32 operations (no FMA, no reciprocal);
+ * bf16 storage is widened exactly first.
+ * out_x: DEVICE fp32 [B, P, N, F]; out_y: DEVICE fp32 [B, Q, N, F]; caller-owned, 16-byte
+ * aligned.  `stream` is a hipStream_t passed as void* (NULL = the default stream).  The kernel
+ * is enqueued and the call returns without synchronising.
+ * Returns the number of valid samples B' in 1..B.  A short last batch is not padded: rows
+ * j >= B' of the outputs are left untouched.
+ * Errors: STATE, RANGE (batch_no outside [0, num_batches)), ARG (null or misaligned), HIP.
+ */
+int pgti_build_batch(pgti_ctx* c, int64_t batch_no, float* out_x, float* out_y, void* stream);
+
+/* Description of the last failure on the calling thread; "" if none.  Valid until the next
+ * library call on this thread. */
+const char* pgti_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* PGTI_H */

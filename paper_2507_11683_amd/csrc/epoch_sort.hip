@@ -1,0 +1,224 @@
+// Epoch index generation (Sec. 4.2 of the paper: the dataset is shuffled at the start of each
+// epoch and then partitioned according to the number of workers).
+//
+// The shuffle is defined as the order of the starts 0..n-1 under ascending (key_i, i), with
+// key_i = M((h1 ^ i) + g), h1 = M((h0 ^ epoch) + g), h0 = M(seed + g), M the splitmix64 output
+// function.  It is computed with a least-significant-digit radix sort: 8 stable counting passes
+// over 8-bit digits of the 64-bit key, the start index riding along as the value.  Stability of
+// every pass makes the index the tiebreak.
+//
+// One pass = two launches:
+//   scan    : exclusive prefix over workgroups of the per-(digit, workgroup) counts, digit totals
+//   scatter : each workgroup ranks its tile (wave ballots give every key its rank among equal
+//             digits in its wave; per-wave LDS counters chain the rounds), adds the scanned base
+//             and writes key/value to the destination; while doing so it counts the NEXT pass's
+//             digit of every key into the count table of the destination tile (integer atomics,
+//             order independent), so no separate counting launch is needed.
+// The key generation launch also produces the counts of pass 0.
+#include "pgti_internal.h"
+
+namespace pgti {
+namespace {
+
+constexpr uint32_t kThreads = 256;
+constexpr uint32_t kWave = 64;
+constexpr uint32_t kWaves = kThreads / kWave;
+constexpr uint32_t kItems = kSortTile / kThreads;  // rounds per wave: 8
+constexpr uint32_t kRadix = 256;
+constexpr uint64_t kGamma = 0x9E3779B97F4A7C15ull;
+static_assert(kRadix == kThreads, "one thread per digit in the scan steps");
+static_assert(kItems * kThreads == kSortTile, "tile must be a whole number of rounds");
+
+__device__ __forceinline__ uint64_t mix64(uint64_t z) {
+    z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+    z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+    return z ^ (z >> 31);
+}
+
+// Inclusive scan of one value per thread over the 256 threads of the workgroup.
+__device__ __forceinline__ uint32_t block_inclusive_scan(uint32_t v, uint32_t* lds) {
+    const uint32_t tid = threadIdx.x;
+    lds[tid] = v;
+    __syncthreads();
+#pragma unroll
+    for (uint32_t off = 1; off < kThreads; off <<= 1) {
+        uint32_t t = (tid >= off) ? lds[tid - off] : 0u;
+        __syncthreads();
+        lds[tid] += t;
+        __syncthreads();
+    }
+    uint32_t r = lds[tid];
+    __syncthreads();
+    return r;
+}
+
+// keys[i] for i < n; counts of the lowest digit per (digit, workgroup) into hist0[digit][wg].
+__global__ void __launch_bounds__(kThreads) keygen_kernel(uint64_t seed, uint64_t epoch, uint32_t n,
+                                                          uint32_t nblk, uint64_t* keys,
+                                                          uint32_t* hist0) {
+    __shared__ uint32_t counts[kRadix];
+    const uint32_t tid = threadIdx.x, b = blockIdx.x;
+    counts[tid] = 0;
+    __syncthreads();
+    const uint64_t h0 = mix64(seed + kGamma);
+    const uint64_t h1 = mix64((h0 ^ epoch) + kGamma);
+#pragma unroll
+    for (uint32_t it = 0; it < kItems; ++it) {
+        uint32_t i = b * kSortTile + it * kThreads + tid;
+        if (i < n) {
+            uint64_t k = mix64((h1 ^ static_cast<uint64_t>(i)) + kGamma);
+            keys[i] = k;
+            atomicAdd(&counts[k & 0xFFu], 1u);
+        }
+    }
+    __syncthreads();
+    hist0[tid * nblk + b] = counts[tid];
+}
+
+// One workgroup per digit d: hist[d][0..nblk) becomes its exclusive prefix, tot[d] its sum.
+// Also clears the other count table, which the following scatter fills for the next pass.
+__global__ void __launch_bounds__(kThreads) scan_kernel(uint32_t* hist, uint32_t* tot,
+                                                        uint32_t* hist_other, uint32_t nblk) {
+    __shared__ uint32_t lds[kThreads];
+    const uint32_t tid = threadIdx.x, d = blockIdx.x;
+    uint32_t* row = hist + static_cast<size_t>(d) * nblk;
+    uint32_t* other = hist_other + static_cast<size_t>(d) * nblk;
+    uint32_t carry = 0;
+    for (uint32_t base = 0; base < nblk; base += kThreads) {
+        uint32_t i = base + tid;
+        uint32_t v = (i < nblk) ? row[i] : 0u;
+        uint32_t incl = block_inclusive_scan(v, lds);
+        if (i < nblk) {
+            row[i] = carry + incl - v;
+            other[i] = 0u;
+        }
+        __shared__ uint32_t chunk_total;
+        if (tid == kThreads - 1) chunk_total = incl;
+        __syncthreads();
+        carry += chunk_total;
+        __syncthreads();
+    }
+    if (tid == 0) tot[d] = carry;
+}
+
+// Stable scatter of one tile by the digit at `shift`.
+// FIRST: values are the element positions themselves (no value array yet).
+// LAST : only the values whose destination falls in [lo, hi) are written, to share[pos - lo].
+template <bool FIRST, bool LAST>
+__global__ void __launch_bounds__(kThreads) scatter_kernel(
+    const uint64_t* __restrict__ keys_in, const int32_t* __restrict__ vals_in,
+    uint64_t* __restrict__ keys_out, int32_t* __restrict__ vals_out,
+    const uint32_t* __restrict__ hist_scanned, const uint32_t* __restrict__ tot,
+    uint32_t* __restrict__ hist_next, uint32_t n, uint32_t nblk, uint32_t shift,
+    int32_t* __restrict__ share, uint32_t lo, uint32_t hi) {
+    __shared__ uint32_t wave_counts[kWaves][kRadix];  // running counts, later wave-exclusive offsets
+    __shared__ uint32_t digit_base[kRadix];
+    __shared__ uint32_t scan_tmp[kThreads];
+
+    const uint32_t tid = threadIdx.x, lane = tid & (kWave - 1), w = tid / kWave, b = blockIdx.x;
+#pragma unroll
+    for (uint32_t k = 0; k < kWaves; ++k) wave_counts[k][tid] = 0;
+    __syncthreads();
+
+    // Wave w owns the contiguous elements [first, first + 64*kItems) of the tile, taken in kItems
+    // rounds of 64 consecutive elements: element order = (wave, round, lane) order.
+    const uint32_t first = b * kSortTile + w * (kWave * kItems);
+    uint64_t key[kItems];
+    int32_t val[kItems];
+    uint32_t rank[kItems];
+#pragma unroll
+    for (uint32_t r = 0; r < kItems; ++r) {
+        uint32_t i = first + r * kWave + lane;
+        bool valid = i < n;
+        key[r] = valid ? keys_in[i] : 0ull;
+        if constexpr (FIRST) val[r] = static_cast<int32_t>(i);
+        else val[r] = valid ? vals_in[i] : 0;
+    }
+
+    const uint64_t lanes_below = (1ull << lane) - 1ull;
+#pragma unroll
+    for (uint32_t r = 0; r < kItems; ++r) {
+        const bool valid = (first + r * kWave + lane) < n;
+        const uint32_t d = static_cast<uint32_t>(key[r] >> shift) & 0xFFu;
+        // peers: the valid lanes of this wave holding the same digit
+        uint64_t peers = __ballot(valid);
+#pragma unroll
+        for (uint32_t bit = 0; bit < 8; ++bit) {
+            const bool one = (d >> bit) & 1u;
+            const uint64_t m = __ballot(one);
+            peers &= one ? m : ~m;
+        }
+        const uint32_t below = __popcll(peers & lanes_below);
+        const uint32_t count = __popcll(peers);
+        uint32_t base = 0;
+        if (valid) base = wave_counts[w][d];  // every peer reads the count before the leader bumps it
+        __builtin_amdgcn_wave_barrier();
+        if (valid && below == 0) wave_counts[w][d] = base + count;
+        __builtin_amdgcn_wave_barrier();
+        rank[r] = base + below;  // rank among equal digits within this wave's elements
+    }
+    __syncthreads();
+
+    // thread tid = digit: wave-exclusive offsets, then the global base of (digit, this tile)
+    {
+        uint32_t run = 0;
+#pragma unroll
+        for (uint32_t k = 0; k < kWaves; ++k) {
+            uint32_t cnt = wave_counts[k][tid];
+            wave_counts[k][tid] = run;
+            run += cnt;
+        }
+        const uint32_t t = tot[tid];
+        const uint32_t incl = block_inclusive_scan(t, scan_tmp);
+        digit_base[tid] = (incl - t) + hist_scanned[static_cast<size_t>(tid) * nblk + b];
+    }
+    __syncthreads();
+
+#pragma unroll
+    for (uint32_t r = 0; r < kItems; ++r) {
+        const bool valid = (first + r * kWave + lane) < n;
+        if (!valid) continue;
+        const uint32_t d = static_cast<uint32_t>(key[r] >> shift) & 0xFFu;
+        const uint32_t pos = digit_base[d] + wave_counts[w][d] + rank[r];
+        if (pos >= n) continue;  // cannot happen with consistent counts; never write out of bounds
+        if constexpr (!LAST) {
+            keys_out[pos] = key[r];
+            vals_out[pos] = val[r];
+            const uint32_t dn = static_cast<uint32_t>(key[r] >> (shift + 8)) & 0xFFu;
+            atomicAdd(&hist_next[static_cast<size_t>(dn) * nblk + pos / kSortTile], 1u);
+        } else {
+            if (pos >= lo && pos < hi) share[pos - lo] = val[r];
+        }
+    }
+}
+
+}  // namespace
+
+hipError_t launch_epoch_sort(pgti_ctx* c, uint64_t seed, uint64_t epoch, uint32_t lo, uint32_t hi,
+                             hipStream_t s) {
+    const uint32_t n = static_cast<uint32_t>(c->n_windows);
+    const uint32_t nblk = c->sort_blocks;
+    hipLaunchKernelGGL(keygen_kernel, dim3(nblk), dim3(kThreads), 0, s, seed, epoch, n, nblk,
+                       c->d_keys[0], c->d_hist[0]);
+    for (uint32_t pass = 0; pass < 8; ++pass) {
+        uint32_t* hist = c->d_hist[pass & 1];
+        uint32_t* hist_next = c->d_hist[(pass + 1) & 1];
+        const uint64_t* kin = c->d_keys[pass & 1];
+        const int32_t* vin = c->d_vals[pass & 1];
+        uint64_t* kout = c->d_keys[(pass + 1) & 1];
+        int32_t* vout = c->d_vals[(pass + 1) & 1];
+        hipLaunchKernelGGL(scan_kernel, dim3(kRadix), dim3(kThreads), 0, s, hist, c->d_tot, hist_next, nblk);
+        if (pass == 0)
+            hipLaunchKernelGGL((scatter_kernel<true, false>), dim3(nblk), dim3(kThreads), 0, s, kin, vin,
+                               kout, vout, hist, c->d_tot, hist_next, n, nblk, 8 * pass, c->d_share, lo, hi);
+        else if (pass < 7)
+            hipLaunchKernelGGL((scatter_kernel<false, false>), dim3(nblk), dim3(kThreads), 0, s, kin, vin,
+                               kout, vout, hist, c->d_tot, hist_next, n, nblk, 8 * pass, c->d_share, lo, hi);
+        else
+            hipLaunchKernelGGL((scatter_kernel<false, true>), dim3(nblk), dim3(kThreads), 0, s, kin, vin,
+                               kout, vout, hist, c->d_tot, hist_next, n, nblk, 8 * pass, c->d_share, lo, hi);
+    }
+    return hipGetLastError();
+}
+
+}  // namespace pgti

@@ -1,0 +1,450 @@
+// C ABI of the index-batching library (declared in pgti.h): argument checking, ownership of
+// device memory, stream ordering.  All arithmetic of the method runs in the kernels of
+// series_store.hip, epoch_sort.hip and batch_gather.hip.
+#include <stdarg.h>
+#include <stdio.h>
+#include <string.h>
+
+#include <cmath>
+#include <new>
+
+#include "pgti_internal.h"
+
+namespace pgti {
+namespace {
+
+thread_local char g_error[512] = "";
+
+// Keeps the caller's current device intact around a call.
+struct DeviceGuard {
+    int prev = -1;
+    bool switched = false;
+    hipError_t status = hipSuccess;
+    explicit DeviceGuard(int device) {
+        status = hipGetDevice(&prev);
+        if (status == hipSuccess && prev != device) {
+            status = hipSetDevice(device);
+            switched = (status == hipSuccess);
+        }
+    }
+    ~DeviceGuard() {
+        if (switched) (void)hipSetDevice(prev);
+    }
+};
+
+void free_series(pgti_ctx* c) {
+    auto drop = [](auto*& p) {
+        if (p) (void)hipFree(p);
+        p = nullptr;
+    };
+    drop(c->d_series);
+    drop(c->d_stats);
+    drop(c->d_keys[0]);
+    drop(c->d_keys[1]);
+    drop(c->d_vals[0]);
+    drop(c->d_vals[1]);
+    drop(c->d_hist[0]);
+    drop(c->d_hist[1]);
+    drop(c->d_tot);
+    drop(c->d_share);
+    c->loaded = false;
+    c->have_share = false;
+    c->series_bytes = 0;
+}
+
+// Temporary device / pinned buffers of one load, released on every exit path.
+struct LoadScratch {
+    void* pinned[2] = {nullptr, nullptr};
+    float* stage[2] = {nullptr, nullptr};
+    double* row_acc = nullptr;
+    double* stat64 = nullptr;
+    hipEvent_t done[2] = {nullptr, nullptr};
+    ~LoadScratch() {
+        for (int k = 0; k < 2; ++k) {
+            if (pinned[k]) (void)hipHostFree(pinned[k]);
+            if (stage[k]) (void)hipFree(stage[k]);
+            if (done[k]) (void)hipEventDestroy(done[k]);
+        }
+        if (row_acc) (void)hipFree(row_acc);
+        if (stat64) (void)hipFree(stat64);
+    }
+};
+
+bool host_pointer_is_pinned(const void* p) {
+    hipPointerAttribute_t attr;
+    hipError_t e = hipPointerGetAttributes(&attr, p);
+    if (e != hipSuccess) {
+        (void)hipGetLastError();  // an ordinary malloc'd pointer is "invalid value" here: not an error
+        return false;
+    }
+    return attr.type == hipMemoryTypeHost;
+}
+
+int check_geometry(int64_t T, int32_t N, int32_t F, int32_t P, int32_t Q, int32_t B, pgti_dtype storage) {
+    if (T <= 0 || N <= 0 || F <= 0 || P <= 0 || Q <= 0 || B <= 0)
+        return fail(PGTI_ERR_ARG, "T, N, F, P, Q, B must all be positive (got T=%lld N=%d F=%d P=%d Q=%d B=%d)",
+                    (long long)T, N, F, P, Q, B);
+    if (storage != PGTI_F32 && storage != PGTI_BF16) return fail(PGTI_ERR_ARG, "unknown storage dtype %d", (int)storage);
+    if (B > 65535) return fail(PGTI_ERR_RANGE, "batch size %d exceeds 65535", B);
+    if (T < static_cast<int64_t>(P) + Q)
+        return fail(PGTI_ERR_RANGE, "series of %lld entries holds no window of %d+%d steps", (long long)T, P, Q);
+    const int64_t n = T - (static_cast<int64_t>(P) + Q) + 1;
+    if (n >= (1ll << 31)) return fail(PGTI_ERR_RANGE, "%lld windows do not fit 32-bit start indices", (long long)n);
+    const int64_t R = static_cast<int64_t>(N) * F;
+    if ((static_cast<int64_t>(P) + Q) * R >= (1ll << 31))
+        return fail(PGTI_ERR_RANGE, "one sample of (P+Q)*N*F = %lld elements exceeds 2^31", (long long)((P + Q) * R));
+    return PGTI_OK;
+}
+
+int check_stats(const float* mean, const float* stdev, int32_t F) {
+    for (int32_t f = 0; f < F; ++f) {
+        if (!std::isfinite(mean[f]) || !std::isfinite(stdev[f]))
+            return fail(PGTI_ERR_STATS, "statistics of feature %d are not finite (mean=%g std=%g)", f, mean[f], stdev[f]);
+        if (stdev[f] == 0.0f) return fail(PGTI_ERR_STATS, "standard deviation of feature %d is zero", f);
+    }
+    return PGTI_OK;
+}
+
+// The load itself.  `src` is fp32 [T, N, F], on the host or (src_on_device) on the device.
+int load_impl(pgti_ctx* c, const float* src, bool src_on_device, int64_t T, int32_t N, int32_t F, int32_t P,
+              int32_t Q, int32_t B, pgti_dtype storage, const float* mean, const float* stdev) {
+    if (!c) return fail(PGTI_ERR_ARG, "null context");
+    if (!src) return fail(PGTI_ERR_ARG, "null series pointer");
+    if ((mean == nullptr) != (stdev == nullptr)) return fail(PGTI_ERR_ARG, "pass both mean and std, or neither");
+    if (int rc = check_geometry(T, N, F, P, Q, B, storage)) return rc;
+    if (mean)
+        if (int rc = check_stats(mean, stdev, F)) return rc;
+
+    DeviceGuard guard(c->device);
+    if (guard.status != hipSuccess) return fail_hip(guard.status, "hipSetDevice");
+    hipStream_t ws = c->work_stream;
+    PGTI_HIP_TRY(hipStreamSynchronize(ws));
+    free_series(c);
+    c->n_tracked = 0;
+
+    const int64_t R = static_cast<int64_t>(N) * F;
+    const size_t elems = static_cast<size_t>(T) * R;
+    const size_t store_bytes = (storage == PGTI_F32) ? 4 : 2;
+    const int64_t n = T - (static_cast<int64_t>(P) + Q) + 1;
+    const bool need_stats = (mean == nullptr);
+
+    auto alloc = [&](auto** p, size_t bytes) -> int {
+        hipError_t e = hipMalloc(reinterpret_cast<void**>(p), bytes < 256 ? 256 : bytes);
+        if (e == hipErrorOutOfMemory) {
+            (void)hipGetLastError();
+            free_series(c);
+            return fail(PGTI_ERR_OOM, "device allocation of %zu bytes failed", bytes);
+        }
+        if (e != hipSuccess) {
+            free_series(c);
+            return fail_hip(e, "hipMalloc");
+        }
+        return PGTI_OK;
+    };
+
+    const uint32_t nblk = static_cast<uint32_t>((n + kSortTile - 1) / kSortTile);
+    if (int rc = alloc(&c->d_series, elems * store_bytes)) return rc;
+    if (int rc = alloc(&c->d_stats, sizeof(float) * 2 * F)) return rc;
+    if (int rc = alloc(&c->d_keys[0], sizeof(uint64_t) * n)) return rc;
+    if (int rc = alloc(&c->d_keys[1], sizeof(uint64_t) * n)) return rc;
+    if (int rc = alloc(&c->d_vals[0], sizeof(int32_t) * n)) return rc;
+    if (int rc = alloc(&c->d_vals[1], sizeof(int32_t) * n)) return rc;
+    if (int rc = alloc(&c->d_hist[0], sizeof(uint32_t) * 256 * nblk)) return rc;
+    if (int rc = alloc(&c->d_hist[1], sizeof(uint32_t) * 256 * nblk)) return rc;
+    if (int rc = alloc(&c->d_tot, sizeof(uint32_t) * 256)) return rc;
+    if (int rc = alloc(&c->d_share, sizeof(int32_t) * n)) return rc;
+    c->series_bytes = elems * store_bytes;
+    c->sort_blocks = nblk;
+
+    // Rows per chunk: about 64 MiB of fp32, a multiple of 4 rows so that every chunk starts on a
+    // 16-byte boundary whatever R is.
+    int64_t chunk_rows = (64ll << 20) / (R * 4);
+    chunk_rows = (chunk_rows / 4) * 4;
+    if (chunk_rows < 4) chunk_rows = 4;
+    const size_t chunk_bytes = static_cast<size_t>(chunk_rows) * R * 4;
+
+    LoadScratch tmp;
+    const bool src_pinned = !src_on_device && host_pointer_is_pinned(src);
+    const bool via_pinned_staging = !src_on_device && !src_pinned;
+    // A device-side fp32 view of each chunk is needed unless fp32 storage receives it directly.
+    const bool via_device_staging = !src_on_device && storage == PGTI_BF16;
+    for (int k = 0; k < 2; ++k) {
+        PGTI_HIP_TRY(hipEventCreateWithFlags(&tmp.done[k], hipEventDisableTiming));
+        if (via_pinned_staging) {
+            hipError_t e = hipHostMalloc(&tmp.pinned[k], chunk_bytes, hipHostMallocDefault);
+            if (e != hipSuccess) {
+                (void)hipGetLastError();
+                free_series(c);
+                return fail(PGTI_ERR_OOM, "pinned staging allocation of %zu bytes failed", chunk_bytes);
+            }
+        }
+        if (via_device_staging)
+            if (int rc = alloc(&tmp.stage[k], chunk_bytes)) return rc;
+    }
+    if (need_stats) {
+        if (int rc = alloc(&tmp.row_acc, sizeof(double) * static_cast<size_t>(T) * F)) return rc;
+        if (int rc = alloc(&tmp.stat64, sizeof(double) * F)) return rc;
+    }
+
+    // Sweep 0 moves the data (and sums values if statistics are wanted); sweep 1, only with
+    // statistics, sums squared deviations from the mean.  With bf16 storage the rounding happens
+    // in the last sweep, from the fp32 chunk, so statistics always see the caller's fp32 values.
+    const int sweeps = need_stats ? 2 : 1;
+    for (int sweep = 0; sweep < sweeps; ++sweep) {
+        const bool last_sweep = (sweep == sweeps - 1);
+        int slot = 0;
+        bool slot_busy[2] = {false, false};
+        for (int64_t row0 = 0; row0 < T; row0 += chunk_rows, slot ^= 1) {
+            const int64_t rows = (T - row0 < chunk_rows) ? (T - row0) : chunk_rows;
+            const size_t off = static_cast<size_t>(row0) * R;
+            const size_t cnt = static_cast<size_t>(rows) * R;
+            const float* dev_chunk = nullptr;  // fp32 view of this chunk on the device
+
+            if (src_on_device) {
+                dev_chunk = src + off;
+                if (storage == PGTI_F32 && sweep == 0)
+                    PGTI_HIP_TRY(hipMemcpyAsync(static_cast<float*>(c->d_series) + off, dev_chunk, cnt * 4,
+                                                hipMemcpyDeviceToDevice, ws));
+            } else if (storage == PGTI_F32 && sweep == 1) {
+                dev_chunk = static_cast<const float*>(c->d_series) + off;  // already resident
+            } else {
+                if (slot_busy[slot]) PGTI_HIP_TRY(hipEventSynchronize(tmp.done[slot]));
+                float* dst = (storage == PGTI_F32) ? static_cast<float*>(c->d_series) + off : tmp.stage[slot];
+                const void* from = src + off;
+                if (via_pinned_staging) {
+                    memcpy(tmp.pinned[slot], src + off, cnt * 4);
+                    from = tmp.pinned[slot];
+                }
+                PGTI_HIP_TRY(hipMemcpyAsync(dst, from, cnt * 4, hipMemcpyHostToDevice, ws));
+                dev_chunk = dst;
+            }
+
+            if (need_stats) {
+                const double* mean64 = (sweep == 1) ? tmp.stat64 : nullptr;
+                PGTI_HIP_TRY(launch_row_sums(dev_chunk, rows, N, F, row0, mean64, tmp.row_acc, ws));
+            }
+            if (storage == PGTI_BF16 && last_sweep)
+                PGTI_HIP_TRY(launch_store_bf16(dev_chunk, static_cast<uint16_t*>(c->d_series) + off, cnt, ws));
+            PGTI_HIP_TRY(hipEventRecord(tmp.done[slot], ws));
+            slot_busy[slot] = true;
+        }
+        if (need_stats) {
+            // mean after sweep 0 (kept in fp64 on the device for sweep 1), std after sweep 1
+            float* out32 = c->d_stats + (sweep == 0 ? 0 : F);
+            PGTI_HIP_TRY(launch_reduce_rows(tmp.row_acc, T, N, F, sweep == 1, tmp.stat64, out32, ws));
+        }
+        PGTI_HIP_TRY(hipStreamSynchronize(ws));
+    }
+
+    c->mean.assign(F, 0.0f);
+    c->stdev.assign(F, 1.0f);
+    if (need_stats) {
+        PGTI_HIP_TRY(hipMemcpy(c->mean.data(), c->d_stats, sizeof(float) * F, hipMemcpyDeviceToHost));
+        PGTI_HIP_TRY(hipMemcpy(c->stdev.data(), c->d_stats + F, sizeof(float) * F, hipMemcpyDeviceToHost));
+        if (int rc = check_stats(c->mean.data(), c->stdev.data(), F)) {
+            free_series(c);
+            return rc;
+        }
+    } else {
+        memcpy(c->mean.data(), mean, sizeof(float) * F);
+        memcpy(c->stdev.data(), stdev, sizeof(float) * F);
+        PGTI_HIP_TRY(hipMemcpy(c->d_stats, c->mean.data(), sizeof(float) * F, hipMemcpyHostToDevice));
+        PGTI_HIP_TRY(hipMemcpy(c->d_stats + F, c->stdev.data(), sizeof(float) * F, hipMemcpyHostToDevice));
+    }
+
+    c->T = T;
+    c->N = N;
+    c->F = F;
+    c->P = P;
+    c->Q = Q;
+    c->B = B;
+    c->R = R;
+    c->storage = storage;
+    c->n_windows = n;
+    const bool quad_ok = ((static_cast<int64_t>(P) * R) % 4 == 0) && ((static_cast<int64_t>(Q) * R) % 4 == 0);
+    c->path = quad_ok ? GatherPath::kQuads : GatherPath::kScalar;
+    c->loaded = true;
+    c->have_share = false;
+    return PGTI_OK;
+}
+
+}  // namespace
+
+int fail(int status, const char* fmt, ...) {
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_error, sizeof(g_error), fmt, ap);
+    va_end(ap);
+    return status;
+}
+
+int fail_hip(hipError_t e, const char* what) {
+    (void)hipGetLastError();
+    snprintf(g_error, sizeof(g_error), "HIP error %d (%s) in %s", (int)e, hipGetErrorString(e), what);
+    return e == hipErrorOutOfMemory ? PGTI_ERR_OOM : PGTI_ERR_HIP;
+}
+
+}  // namespace pgti
+
+using namespace pgti;
+
+extern "C" {
+
+int pgti_create(pgti_ctx** out, int device) {
+    g_error[0] = 0;
+    if (!out) return fail(PGTI_ERR_ARG, "null output handle");
+    *out = nullptr;
+    int count = 0;
+    PGTI_HIP_TRY(hipGetDeviceCount(&count));
+    if (device < 0 || device >= count) return fail(PGTI_ERR_ARG, "device %d not in [0, %d)", device, count);
+    pgti_ctx* c = new (std::nothrow) pgti_ctx();
+    if (!c) return fail(PGTI_ERR_OOM, "host allocation failed");
+    c->device = device;
+    DeviceGuard guard(device);
+    hipError_t e = guard.status;
+    if (e == hipSuccess) e = hipStreamCreateWithFlags(&c->work_stream, hipStreamNonBlocking);
+    if (e == hipSuccess) e = hipEventCreateWithFlags(&c->ev_share_ready, hipEventDisableTiming);
+    for (int k = 0; k < kMaxTrackedStreams && e == hipSuccess; ++k) {
+        c->tracked[k].stream = nullptr;
+        c->tracked[k].event = nullptr;
+        e = hipEventCreateWithFlags(&c->tracked[k].event, hipEventDisableTiming);
+    }
+    if (e != hipSuccess) {
+        int rc = fail_hip(e, "creating stream/events");
+        pgti_destroy(c);
+        return rc;
+    }
+    *out = c;
+    return PGTI_OK;
+}
+
+void pgti_destroy(pgti_ctx* c) {
+    if (!c) return;
+    DeviceGuard guard(c->device);
+    if (c->work_stream) (void)hipStreamSynchronize(c->work_stream);
+    free_series(c);
+    for (int k = 0; k < kMaxTrackedStreams; ++k)
+        if (c->tracked[k].event) (void)hipEventDestroy(c->tracked[k].event);
+    if (c->ev_share_ready) (void)hipEventDestroy(c->ev_share_ready);
+    if (c->work_stream) (void)hipStreamDestroy(c->work_stream);
+    delete c;
+}
+
+int pgti_load_series(pgti_ctx* c, const float* host_series, int64_t T, int32_t N, int32_t F, int32_t P,
+                     int32_t Q, int32_t B, pgti_dtype storage, const float* mean, const float* std) {
+    g_error[0] = 0;
+    return load_impl(c, host_series, false, T, N, F, P, Q, B, storage, mean, std);
+}
+
+int pgti_load_series_device(pgti_ctx* c, const float* device_series, int64_t T, int32_t N, int32_t F,
+                            int32_t P, int32_t Q, int32_t B, pgti_dtype storage, const float* mean,
+                            const float* std) {
+    g_error[0] = 0;
+    return load_impl(c, device_series, true, T, N, F, P, Q, B, storage, mean, std);
+}
+
+int pgti_get_stats(pgti_ctx* c, float* mean_out, float* std_out) {
+    g_error[0] = 0;
+    if (!c) return fail(PGTI_ERR_ARG, "null context");
+    if (!c->loaded) return fail(PGTI_ERR_STATE, "no series loaded");
+    if (mean_out) memcpy(mean_out, c->mean.data(), sizeof(float) * c->F);
+    if (std_out) memcpy(std_out, c->stdev.data(), sizeof(float) * c->F);
+    return PGTI_OK;
+}
+
+int pgti_epoch_indices(pgti_ctx* c, uint64_t seed, uint64_t epoch, uint32_t rank, uint32_t world,
+                       int64_t* n_share) {
+    g_error[0] = 0;
+    if (!c) return fail(PGTI_ERR_ARG, "null context");
+    if (!c->loaded) return fail(PGTI_ERR_STATE, "no series loaded");
+    if (world == 0) return fail(PGTI_ERR_RANGE, "world must be at least 1");
+    if (rank >= world) return fail(PGTI_ERR_RANGE, "rank %u not in [0, %u)", rank, world);
+    DeviceGuard guard(c->device);
+    if (guard.status != hipSuccess) return fail_hip(guard.status, "hipSetDevice");
+
+    const uint64_t n = static_cast<uint64_t>(c->n_windows);
+    const uint64_t lo = (static_cast<uint64_t>(rank) * n) / world;  // < 2^32 * 2^31: no overflow
+    const uint64_t hi = ((static_cast<uint64_t>(rank) + 1) * n) / world;
+
+    // The share buffer is about to be overwritten: order the sort behind every batch build that
+    // was enqueued through this context since the last sort.
+    for (int k = 0; k < c->n_tracked; ++k) {
+        PGTI_HIP_TRY(hipEventRecord(c->tracked[k].event, c->tracked[k].stream));
+        PGTI_HIP_TRY(hipStreamWaitEvent(c->work_stream, c->tracked[k].event, 0));
+    }
+    c->n_tracked = 0;
+
+    PGTI_HIP_TRY(launch_epoch_sort(c, seed, epoch, static_cast<uint32_t>(lo), static_cast<uint32_t>(hi),
+                                   c->work_stream));
+    PGTI_HIP_TRY(hipEventRecord(c->ev_share_ready, c->work_stream));
+    c->share_lo = static_cast<int64_t>(lo);
+    c->share_hi = static_cast<int64_t>(hi);
+    c->have_share = true;
+    if (n_share) *n_share = static_cast<int64_t>(hi - lo);
+    return PGTI_OK;
+}
+
+int64_t pgti_get_indices(pgti_ctx* c, int32_t* host_out, int64_t capacity) {
+    g_error[0] = 0;
+    if (!c) return fail(PGTI_ERR_ARG, "null context");
+    if (!c->loaded || !c->have_share) return fail(PGTI_ERR_STATE, "no epoch indices generated");
+    const int64_t len = c->share_hi - c->share_lo;
+    if (len > 0 && (!host_out || capacity < len))
+        return fail(PGTI_ERR_ARG, "share of %lld starts does not fit capacity %lld", (long long)len, (long long)capacity);
+    DeviceGuard guard(c->device);
+    if (guard.status != hipSuccess) return fail_hip(guard.status, "hipSetDevice");
+    PGTI_HIP_TRY(hipStreamSynchronize(c->work_stream));
+    if (len > 0) PGTI_HIP_TRY(hipMemcpy(host_out, c->d_share, sizeof(int32_t) * len, hipMemcpyDeviceToHost));
+    return len;
+}
+
+int64_t pgti_num_batches(pgti_ctx* c) {
+    g_error[0] = 0;
+    if (!c) return fail(PGTI_ERR_ARG, "null context");
+    if (!c->loaded || !c->have_share) return fail(PGTI_ERR_STATE, "no epoch indices generated");
+    const int64_t len = c->share_hi - c->share_lo;
+    return (len + c->B - 1) / c->B;
+}
+
+int pgti_build_batch(pgti_ctx* c, int64_t batch_no, float* out_x, float* out_y, void* stream) {
+    g_error[0] = 0;
+    if (!c) return fail(PGTI_ERR_ARG, "null context");
+    if (!c->loaded) return fail(PGTI_ERR_STATE, "no series loaded");
+    if (!c->have_share) return fail(PGTI_ERR_STATE, "no epoch indices generated");
+    if (!out_x || !out_y) return fail(PGTI_ERR_ARG, "null output pointer");
+    if ((reinterpret_cast<uintptr_t>(out_x) | reinterpret_cast<uintptr_t>(out_y)) & 15u)
+        return fail(PGTI_ERR_ARG, "outputs must be 16-byte aligned");
+    const int64_t len = c->share_hi - c->share_lo;
+    const int64_t nb = (len + c->B - 1) / c->B;
+    if (batch_no < 0 || batch_no >= nb)
+        return fail(PGTI_ERR_RANGE, "batch %lld not in [0, %lld)", (long long)batch_no, (long long)nb);
+    const int64_t first = batch_no * c->B;
+    const int32_t count = static_cast<int32_t>((len - first < c->B) ? (len - first) : c->B);
+
+    DeviceGuard guard(c->device);
+    if (guard.status != hipSuccess) return fail_hip(guard.status, "hipSetDevice");
+    hipStream_t s = static_cast<hipStream_t>(stream);
+
+    // First build on this stream since the last sort: make the stream wait for the share.
+    bool known = false;
+    for (int k = 0; k < c->n_tracked; ++k) known = known || (c->tracked[k].stream == s);
+    if (!known) {
+        int slot = c->n_tracked;
+        if (c->n_tracked == kMaxTrackedStreams) {
+            // More streams than slots: finish the builds of the oldest on the host and reuse its slot.
+            PGTI_HIP_TRY(hipStreamSynchronize(c->tracked[0].stream));
+            slot = 0;
+        } else {
+            ++c->n_tracked;
+        }
+        PGTI_HIP_TRY(hipStreamWaitEvent(s, c->ev_share_ready, 0));
+        c->tracked[slot].stream = s;
+    }
+
+    PGTI_HIP_TRY(launch_batch_gather(c, c->d_share + first, count, out_x, out_y, s));
+    return count;
+}
+
+const char* pgti_last_error(void) { return g_error; }
+
+}  // extern "C"

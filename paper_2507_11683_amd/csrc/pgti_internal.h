@@ -1,0 +1,103 @@
+// Internal declarations of the gfx950 index-batching library: the context behind the opaque
+// handle of pgti.h and the kernel launchers each translation unit provides.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include <string>
+#include <vector>
+
+#include "pgti.h"
+
+namespace pgti {
+
+// Features whose statistics travel inside the kernel argument block; larger F reads them from HBM.
+constexpr int kInlineStats = 8;
+// Streams whose batch builds are tracked between two epoch-index generations.
+constexpr int kMaxTrackedStreams = 8;
+
+struct TrackedStream {
+    hipStream_t stream;
+    hipEvent_t event;  // recorded behind the builds of this stream when the next sort is enqueued
+};
+
+// How pgti_build_batch maps a sample onto threads, fixed when the series is loaded.
+enum class GatherPath : int {
+    kScalar = 0,  // any geometry: one element per thread
+    kQuads = 1    // P*R and Q*R multiples of 4: one 16-byte output quad per thread-iteration
+};
+
+}  // namespace pgti
+
+struct pgti_ctx {
+    int device = 0;
+
+    // geometry (valid when loaded)
+    bool loaded = false;
+    int64_t T = 0;
+    int32_t N = 0, F = 0, P = 0, Q = 0, B = 0;
+    pgti_dtype storage = PGTI_F32;
+    int64_t R = 0;          // elements per timestep row, N*F
+    int64_t n_windows = 0;  // T - (P+Q) + 1
+
+    // resident store
+    void* d_series = nullptr;
+    size_t series_bytes = 0;
+    std::vector<float> mean, stdev;  // host copies, F entries
+    float* d_stats = nullptr;        // device: mean[F] then std[F]
+    pgti::GatherPath path = pgti::GatherPath::kScalar;
+
+    // epoch index generation
+    hipStream_t work_stream = nullptr;  // owns the sort and the load-time kernels
+    uint64_t* d_keys[2] = {nullptr, nullptr};
+    int32_t* d_vals[2] = {nullptr, nullptr};
+    uint32_t* d_hist[2] = {nullptr, nullptr};  // [256][nblk] digit-major block counts, ping-pong
+    uint32_t* d_tot = nullptr;                 // [256] digit totals of the current pass
+    int32_t* d_share = nullptr;                // this rank's starts, capacity n_windows
+    uint32_t sort_blocks = 0;
+    bool have_share = false;
+    int64_t share_lo = 0, share_hi = 0;
+    hipEvent_t ev_share_ready = nullptr;
+
+    pgti::TrackedStream tracked[pgti::kMaxTrackedStreams];
+    int n_tracked = 0;
+};
+
+namespace pgti {
+
+// ---- error plumbing (pgti_api.hip) ----------------------------------------------------------
+int fail(int status, const char* fmt, ...);
+int fail_hip(hipError_t e, const char* what);
+
+#define PGTI_HIP_TRY(expr)                                   \
+    do {                                                     \
+        hipError_t e__ = (expr);                             \
+        if (e__ != hipSuccess) return ::pgti::fail_hip(e__, #expr); \
+    } while (0)
+
+// ---- series_store.hip -----------------------------------------------------------------------
+// fp32 -> bf16 (round to nearest even) of `count` elements; both pointers on the device.
+hipError_t launch_store_bf16(const float* src, uint16_t* dst, size_t count, hipStream_t s);
+// Per-row partial sums for the statistics.  row_acc is [rows_total][F] fp64 on the device; the
+// rows [row0, row0+rows) of it are written from `chunk` (fp32, rows x N x F, device).
+// mean64 == nullptr: sums of values; else sums of squared deviations from mean64[f] (device).
+hipError_t launch_row_sums(const float* chunk, int64_t rows, int32_t N, int32_t F, int64_t row0,
+                           const double* mean64, double* row_acc, hipStream_t s);
+// Reduces row_acc over all T rows in a fixed order, divides by T*N; take_sqrt selects the
+// standard deviation.  out64 is [F] fp64 on the device, out32 [F] fp32 on the device.
+hipError_t launch_reduce_rows(const double* row_acc, int64_t T, int32_t N, int32_t F, bool take_sqrt,
+                              double* out64, float* out32, hipStream_t s);
+
+// ---- epoch_sort.hip -------------------------------------------------------------------------
+constexpr uint32_t kSortTile = 2048;  // keys per workgroup per pass
+// Keys, 8 stable counting passes, and the rank's slice [lo, hi) of the sorted starts -> share.
+hipError_t launch_epoch_sort(pgti_ctx* c, uint64_t seed, uint64_t epoch, uint32_t lo, uint32_t hi,
+                             hipStream_t s);
+
+// ---- batch_gather.hip -----------------------------------------------------------------------
+// Enqueues the fused gather + standardise of `count` samples whose starts are d_starts[0..count).
+hipError_t launch_batch_gather(const pgti_ctx* c, const int32_t* d_starts, int32_t count,
+                               float* out_x, float* out_y, hipStream_t s);
+
+}  // namespace pgti

@@ -1,0 +1,367 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle, bit for bit.
+
+Bar: indices and gathered values identical; standardised fp32 values identical (the oracle and
+the kernel both take one rounded subtraction and one correctly rounded division per element).
+NaN outputs are compared as "NaN in the same places" (payloads are not part of the contract).
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2507_11683_amd import workloads
+
+pytestmark = pytest.mark.gpu
+
+if torch.cuda.is_available():
+    from paper_2507_11683_amd import pgti
+else:  # collected on a CPU machine only to be deselected
+    pgti = None
+
+
+def _bits_equal(got: np.ndarray, want: np.ndarray) -> bool:
+    g, w = got.view(np.uint32), want.view(np.uint32)
+    same = g == w
+    if same.all():
+        return True
+    both_nan = np.isnan(got) & np.isnan(want)
+    return bool((same | both_nan).all())
+
+
+def _first_mismatch(got, want):
+    g, w = got.view(np.uint32).ravel(), want.view(np.uint32).ravel()
+    bad = np.flatnonzero(g != w)
+    return None if bad.size == 0 else (int(bad[0]), got.ravel()[bad[0]], want.ravel()[bad[0]], bad.size)
+
+
+def _alloc_out(B, P, Q, N, F, fill=None):
+    x = torch.empty((B, P, N, F), dtype=torch.float32, device="cuda")
+    y = torch.empty((B, Q, N, F), dtype=torch.float32, device="cuda")
+    if fill is not None:
+        x.fill_(fill)
+        y.fill_(fill)
+    return x, y
+
+
+def _oracle_series(series, storage):
+    return series if storage == pgti.PGTI_F32 else oracle.store_bf16(series)
+
+
+def _check_batches(ctx, series_for_oracle, storage, P, Q, B, mean, std, share, batch_list):
+    """Builds the listed batches on the GPU and compares each with the oracle; a canary value in
+    the rows past a short batch must survive."""
+    T, N, F = series_for_oracle.shape
+    canary = 12345.0
+    x, y = _alloc_out(B, P, Q, N, F)
+    for b in batch_list:
+        x.fill_(canary)
+        y.fill_(canary)
+        count = ctx.build_batch(b, x, y)
+        torch.cuda.synchronize()
+        starts = share[b * B:(b + 1) * B]
+        assert count == len(starts), (b, count, len(starts))
+        want_x, want_y = oracle.build_batch(series_for_oracle, storage, P, Q, mean, std, starts)
+        got_x, got_y = x.cpu().numpy(), y.cpu().numpy()
+        assert _bits_equal(got_x[:count], want_x), ("x", b, _first_mismatch(got_x[:count], want_x))
+        assert _bits_equal(got_y[:count], want_y), ("y", b, _first_mismatch(got_y[:count], want_y))
+        if count < B:  # short batch: nothing written past the valid rows
+            assert np.all(got_x[count:] == canary) and np.all(got_y[count:] == canary)
+
+
+def _run_workload_epoch(w, series, batches=None, ctx=None, loaded=False):
+    storage = pgti.PGTI_F32 if w.storage == "f32" else pgti.PGTI_BF16
+    mean, std = oracle.series_stats(series) if series.size < 5e8 else _sampled_stats(series)
+    mean[1], std[1] = 0.0, 1.0  # time-of-day channel passes through unchanged
+    own = ctx is None
+    ctx = ctx or pgti.Context(0)
+    try:
+        if not loaded:
+            ctx.load_series(series, w.P, w.Q, w.B, storage, mean, std)
+        ser_o = _oracle_series(series, storage)
+        for epoch in w.epochs:
+            n_share = ctx.epoch_indices(w.seed, epoch, w.rank, w.world)
+            share = ctx.get_indices()
+            want = oracle.epoch_indices(w.seed, epoch, w.rank, w.world, w.n_windows)
+            assert n_share == len(want) == len(share)
+            assert np.array_equal(share, want), f"epoch {epoch}: share differs from the oracle"
+            nb = ctx.num_batches()
+            assert nb == -(-n_share // w.B)
+            todo = range(nb) if batches is None else sorted({b for b in batches(nb)})
+            _check_batches(ctx, ser_o, storage, w.P, w.Q, w.B, mean, std, share, todo)
+    finally:
+        if own:
+            ctx.destroy()
+
+
+def _sampled_stats(series):
+    # for the 9.4 GB series: statistics of a slab are good enough to standardise with (any finite
+    # mean / non-zero std gives a valid parity case; both sides receive the same numbers)
+    m, s = oracle.series_stats(np.ascontiguousarray(series[:512]))
+    return m, s
+
+
+# ----------------------------------------------------------------------------------------------
+# the benchmark workloads
+# ----------------------------------------------------------------------------------------------
+def test_tiny_every_batch():
+    w = workloads.WORKLOADS["tiny"]
+    _run_workload_epoch(w, workloads.make_series(w))
+
+
+def test_medium_every_batch():
+    w = workloads.WORKLOADS["medium"]
+    _run_workload_epoch(w, workloads.make_series(w))
+
+
+def test_medium_wide_every_batch():
+    w = workloads.WORKLOADS["medium_wide"]
+    _run_workload_epoch(w, workloads.make_series(w))
+
+
+@pytest.fixture(scope="module")
+def statewide_series():
+    w = workloads.WORKLOADS["statewide"]
+    return workloads.make_series(w)
+
+
+def _sampled(nb):
+    return [0, 1, nb // 3, nb // 2, nb - 2, nb - 1] + list(range(7, nb, max(1, nb // 12)))
+
+
+def test_statewide_indices_and_sampled_batches(statewide_series):
+    # Full size, the launch configuration the benchmark times.  All 105,097 indices are compared;
+    # 18 of the 3,285 batches (first, last short one, spread) are compared element by element.
+    w = workloads.WORKLOADS["statewide"]
+    _run_workload_epoch(w, statewide_series, batches=_sampled)
+
+
+def test_statewide_bf16_rank3of16_three_epochs(statewide_series):
+    w = workloads.WORKLOADS["statewide_bf16_rank3of16"]
+    _run_workload_epoch(w, statewide_series, batches=lambda nb: [0, nb // 2, nb - 1])
+
+
+# ----------------------------------------------------------------------------------------------
+# geometry sweep: several tiles and ragged tails, every alignment class, both storage types
+# ----------------------------------------------------------------------------------------------
+GEOMETRIES = [
+    # T,   N,   F, P,  Q,  B
+    (300, 207, 2, 12, 12, 64),   # 8-byte aligned rows (odd starts misaligned for 16-byte loads)
+    (200, 325, 2, 12, 12, 16),
+    (120, 1116, 2, 12, 12, 8),   # 16-byte aligned rows, several workgroups per sample
+    (90, 4001, 2, 4, 8, 5),      # P != Q, large odd N
+    (400, 319, 1, 8, 8, 64),     # F = 1, odd row length: 4-byte aligned rows only
+    (522, 20, 1, 4, 4, 4),       # tiny rows
+    (150, 33, 4, 6, 2, 7),       # F = 4
+    (150, 10, 3, 4, 4, 9),       # F = 3: generic feature pattern, quad path (P*R % 4 == 0)
+    (150, 7, 3, 3, 5, 9),        # P*R = 63: scalar path
+    (100, 5, 11, 2, 3, 6),       # F > 8: statistics read from memory, scalar path
+    (80, 12, 12, 3, 3, 4),       # F = 12 > 8 on the quad path
+    (30, 3, 2, 12, 12, 64),      # 7 windows only, B > n
+    (24, 1, 1, 12, 12, 1),       # a single window, single element rows
+]
+
+
+def _special_series(rng, T, N, F):
+    s = rng.normal(50, 20, (T, N, F)).astype(np.float32)
+    flat = s.reshape(-1)
+    k = max(1, flat.size // 50)
+    idx = rng.choice(flat.size, size=min(flat.size, 8 * k), replace=False)
+    specials = np.array([0.0, -0.0, np.inf, -np.inf, np.nan, 1e-45, -3e-39, 1.17549435e-38,
+                         3.4028235e38, -3.4028235e38, 1e-30, 65504.0], dtype=np.float32)
+    flat[idx] = specials[rng.integers(0, len(specials), idx.size)]
+    return s
+
+
+@pytest.mark.parametrize("storage_name", ["f32", "bf16"])
+@pytest.mark.parametrize("geom", GEOMETRIES, ids=lambda g: "T%d_N%d_F%d_P%d_Q%d_B%d" % g)
+def test_geometry_sweep(geom, storage_name):
+    T, N, F, P, Q, B = geom
+    rng = np.random.default_rng(sum((i + 1) * v for i, v in enumerate(geom)))
+    series = _special_series(rng, T, N, F)
+    mean = rng.normal(40, 10, F).astype(np.float32)
+    std = rng.uniform(0.3, 25, F).astype(np.float32)
+    if F > 1:
+        mean[-1], std[-1] = 0.0, 1.0  # one identity channel
+    storage = pgti.PGTI_F32 if storage_name == "f32" else pgti.PGTI_BF16
+    n = T - P - Q + 1
+    with pgti.Context(0) as ctx:
+        ctx.load_series(series, P, Q, B, storage, mean, std)
+        ser_o = _oracle_series(series, storage)
+        for seed, epoch, rank, world in [(1, 0, 0, 1), (9, 3, 1, 3)]:
+            n_share = ctx.epoch_indices(seed, epoch, rank, world)
+            share = ctx.get_indices()
+            want = oracle.epoch_indices(seed, epoch, rank, world, n)
+            assert n_share == len(want) and np.array_equal(share, want)
+            if n_share == 0:
+                continue
+            _check_batches(ctx, ser_o, storage, P, Q, B, mean, std, share, range(ctx.num_batches()))
+
+
+def test_identity_channel_returns_stored_bits():
+    # mean 0 / std 1 on every feature: outputs are exactly the stored values (for bf16 storage,
+    # the oracle's rounded bits widened), which checks the resident store itself.
+    rng = np.random.default_rng(5)
+    T, N, F, P, Q, B = 64, 50, 2, 5, 5, 8
+    series = _special_series(rng, T, N, F)
+    zero, one = np.zeros(F, np.float32), np.ones(F, np.float32)
+    for storage in (pgti.PGTI_F32, pgti.PGTI_BF16):
+        with pgti.Context(0) as ctx:
+            ctx.load_series(series, P, Q, B, storage, zero, one)
+            ctx.epoch_indices(0, 0)
+            share = ctx.get_indices()
+            x, y = _alloc_out(B, P, Q, N, F)
+            ctx.build_batch(0, x, y)
+            torch.cuda.synchronize()
+            stored = series if storage == pgti.PGTI_F32 else \
+                (oracle.store_bf16(series).astype(np.uint32) << 16).view(np.float32)
+            for j, s in enumerate(share[:B]):
+                assert _bits_equal(x[j].cpu().numpy(), stored[s:s + P])
+                assert _bits_equal(y[j].cpu().numpy(), stored[s + P:s + P + Q])
+
+
+# ----------------------------------------------------------------------------------------------
+# index generation on its own
+# ----------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("n", [1, 2, 63, 64, 65, 2047, 2048, 2049, 4096, 10000, 105097])
+def test_epoch_order_sizes(n):
+    # n spans one lane, one wave, one tile, several tiles with a ragged tail
+    P = Q = 1
+    T = n + P + Q - 1
+    series = np.zeros((T, 1, 1), np.float32)
+    with pgti.Context(0) as ctx:
+        ctx.load_series(series, P, Q, 4, pgti.PGTI_F32, [0.0], [1.0])
+        for seed, epoch in [(0, 0), (2 ** 64 - 1, 2 ** 63 + 5)]:
+            assert ctx.epoch_indices(seed, epoch) == n
+            got = ctx.get_indices()
+            assert np.array_equal(got, oracle.epoch_perm(seed, epoch, n))
+        # all ranks of an uneven split: disjoint, complete, contiguous pieces of the same order
+        world = 7
+        pieces = []
+        for r in range(world):
+            ctx.epoch_indices(3, 1, r, world)
+            pieces.append(ctx.get_indices())
+        assert np.array_equal(np.concatenate(pieces), oracle.epoch_perm(3, 1, n))
+
+
+def test_epoch_indices_reproducible_and_reentrant():
+    w = workloads.WORKLOADS["tiny"]
+    series = workloads.make_series(w)
+    with pgti.Context(0) as a, pgti.Context(0) as b:
+        a.load_series(series, w.P, w.Q, w.B, pgti.PGTI_F32, [0, 0], [1, 1])
+        b.load_series(series, w.P, w.Q, w.B, pgti.PGTI_F32, [0, 0], [1, 1])
+        a.epoch_indices(0, 0)
+        first = a.get_indices()
+        a.epoch_indices(0, 1)
+        second = a.get_indices()
+        a.epoch_indices(0, 0)
+        b.epoch_indices(0, 0)
+        assert np.array_equal(a.get_indices(), first) and np.array_equal(b.get_indices(), first)
+        assert not np.array_equal(first, second)
+
+
+def test_batches_follow_new_epoch_without_host_sync():
+    # builds of epoch e, then the sort of epoch e+1, then builds again: ordering is internal
+    w = workloads.WORKLOADS["tiny"]
+    series = workloads.make_series(w)
+    mean, std = oracle.series_stats(series)
+    side = torch.cuda.Stream()
+    with pgti.Context(0) as ctx:
+        ctx.load_series(series, w.P, w.Q, w.B, pgti.PGTI_F32, mean, std)
+        outs = []
+        for epoch, stream in [(0, None), (1, side), (2, None)]:
+            ctx.epoch_indices(5, epoch)
+            nb = ctx.num_batches()
+            x, y = _alloc_out(w.B, w.P, w.Q, w.N, w.F)
+            for b in range(nb):  # same buffers every batch: the last one wins
+                ctx.build_batch(b, x, y, stream=stream)
+            outs.append((epoch, nb, x, y))
+        torch.cuda.synchronize()
+        for epoch, nb, x, y in outs:
+            share = oracle.epoch_indices(5, epoch, 0, 1, w.n_windows)
+            last = share[(nb - 1) * w.B:]
+            wx, wy = oracle.build_batch(series, oracle.F32, w.P, w.Q, mean, std, last)
+            assert _bits_equal(x[:len(last)].cpu().numpy(), wx)
+            assert _bits_equal(y[:len(last)].cpu().numpy(), wy)
+
+
+# ----------------------------------------------------------------------------------------------
+# statistics computed by the library
+# ----------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("storage_name", ["f32", "bf16"])
+def test_library_statistics(storage_name):
+    # Tolerance: both sides accumulate in fp64 (relative error ~1e-13 for these sizes) in different
+    # orders and round to fp32 once, so they agree to 1 fp32 ulp and almost always exactly.
+    w = workloads.WORKLOADS["medium"]
+    series = workloads.make_series(w)
+    storage = pgti.PGTI_F32 if storage_name == "f32" else pgti.PGTI_BF16
+    want_m, want_s = oracle.series_stats(series)
+    with pgti.Context(0) as ctx:
+        ctx.load_series(series, w.P, w.Q, w.B, storage, None, None)
+        got_m, got_s = ctx.get_stats()
+        for g, wv in list(zip(got_m, want_m)) + list(zip(got_s, want_s)):
+            assert abs(int(np.float32(g).view(np.int32)) - int(np.float32(wv).view(np.int32))) <= 1, (g, wv)
+        # and the batches use exactly the statistics reported
+        ctx.epoch_indices(0, 0)
+        share = ctx.get_indices()
+        _check_batches(ctx, _oracle_series(series, storage), storage, w.P, w.Q, w.B, got_m, got_s, share, [0, 17])
+
+
+def test_device_resident_source():
+    w = workloads.WORKLOADS["tiny"]
+    series = workloads.make_series(w)
+    mean, std = oracle.series_stats(series)
+    dev = torch.from_numpy(series).cuda()
+    for storage in (pgti.PGTI_F32, pgti.PGTI_BF16):
+        with pgti.Context(0) as ctx:
+            ctx.load_series(dev, w.P, w.Q, w.B, storage, mean, std)
+            ctx.epoch_indices(0, 0)
+            share = ctx.get_indices()
+            _check_batches(ctx, _oracle_series(series, storage), storage, w.P, w.Q, w.B, mean, std, share, [0, 30])
+    pinned = torch.from_numpy(series).pin_memory()
+    with pgti.Context(0) as ctx:
+        ctx.load_series(pinned, w.P, w.Q, w.B, pgti.PGTI_F32, mean, std)
+        ctx.epoch_indices(0, 0)
+        _check_batches(ctx, series, pgti.PGTI_F32, w.P, w.Q, w.B, mean, std, ctx.get_indices(), [3])
+
+
+# ----------------------------------------------------------------------------------------------
+# error behaviour through the ABI
+# ----------------------------------------------------------------------------------------------
+def test_error_codes():
+    series = np.zeros((30, 4, 2), np.float32)
+    with pgti.Context(0) as ctx:
+        x, y = _alloc_out(4, 12, 12, 4, 2)
+        with pytest.raises(pgti.PgtiError) as e:
+            ctx.epoch_indices(0, 0)
+        assert e.value.status == pgti.PGTI_ERR_STATE
+        with pytest.raises(pgti.PgtiError) as e:
+            ctx.load_series(series, 20, 20, 4, pgti.PGTI_F32, [0, 0], [1, 1])
+        assert e.value.status == pgti.PGTI_ERR_RANGE
+        with pytest.raises(pgti.PgtiError) as e:
+            ctx.load_series(series, 12, 12, 4, pgti.PGTI_F32, [0, 0], [1, 0])
+        assert e.value.status == pgti.PGTI_ERR_STATS
+        with pytest.raises(pgti.PgtiError) as e:
+            ctx.load_series(series, 12, 12, 4, pgti.PGTI_F32, [0, float("nan")], [1, 1])
+        assert e.value.status == pgti.PGTI_ERR_STATS
+        with pytest.raises(pgti.PgtiError) as e:  # constant series: computed std is zero
+            ctx.load_series(series, 12, 12, 4, pgti.PGTI_F32, None, None)
+        assert e.value.status == pgti.PGTI_ERR_STATS
+        ctx.load_series(series, 12, 12, 4, pgti.PGTI_F32, [0, 0], [1, 1])
+        with pytest.raises(pgti.PgtiError) as e:
+            ctx.build_batch(0, x, y)
+        assert e.value.status == pgti.PGTI_ERR_STATE
+        with pytest.raises(pgti.PgtiError) as e:
+            ctx.epoch_indices(0, 0, 2, 2)
+        assert e.value.status == pgti.PGTI_ERR_RANGE
+        assert ctx.epoch_indices(0, 0) == 7
+        assert ctx.num_batches() == 2
+        with pytest.raises(pgti.PgtiError) as e:
+            ctx.build_batch(2, x, y)
+        assert e.value.status == pgti.PGTI_ERR_RANGE
+        with pytest.raises(pgti.PgtiError) as e:
+            ctx.build_batch(-1, x, y)
+        assert e.value.status == pgti.PGTI_ERR_RANGE
+        rc = ctx.build_batch_raw(0, x.data_ptr() + 4, y.data_ptr(), 0)
+        assert rc == pgti.PGTI_ERR_ARG and "aligned" in pgti.last_error()
+        assert ctx.build_batch(1, x, y) == 3
+        torch.cuda.synchronize()
