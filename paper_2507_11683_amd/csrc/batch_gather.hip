@@ -20,8 +20,8 @@ namespace {
 constexpr int kThreads = 256;
 
 typedef float f32x4 __attribute__((ext_vector_type(4)));
-typedef float f32x2 __attribute__((ext_vector_type(2)));
-typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+typedef float f32x4_a4 __attribute__((ext_vector_type(4), aligned(4)));       // element-aligned quad
+typedef uint32_t u32x2_a2 __attribute__((ext_vector_type(2), aligned(2)));    // four bf16, element aligned
 
 struct GatherArgs {
     const void* series;     // resident [T, R], fp32 or bf16
@@ -50,36 +50,21 @@ __device__ __forceinline__ int64_t span_offset(const GatherArgs& a, uint32_t j) 
     return static_cast<int64_t>(start) * a.R;
 }
 
-// Loads the 4 consecutive stored elements that start at element offset `e` of the series.
-// ALIGN_CLASS 0: e % 4 == 0 (one vector load); 2: e % 4 == 2 (two half loads); 1: odd (four).
-template <int STORE_BYTES, int ALIGN_CLASS>
+// Loads the 4 consecutive stored elements that start at element offset `e` of the series as one
+// vector access.  A span starts at start*R elements, so it is only element aligned in general
+// (R = 414 floats: 8 bytes; R = 319: 4 bytes); global memory on gfx950 serves such vector loads,
+// hence the under-aligned vector types.  STREAM adds the non-temporal hint: the series is far
+// larger than the caches and every byte is used once per launch.
+template <int STORE_BYTES, bool STREAM>
 __device__ __forceinline__ f32x4 load_quad(const void* series, int64_t e) {
-    f32x4 v;
     if constexpr (STORE_BYTES == 4) {
-        const float* p = static_cast<const float*>(series) + e;
-        if constexpr (ALIGN_CLASS == 0) {
-            v = *reinterpret_cast<const f32x4*>(p);
-        } else if constexpr (ALIGN_CLASS == 2) {
-            f32x2 a = *reinterpret_cast<const f32x2*>(p);
-            f32x2 b = *reinterpret_cast<const f32x2*>(p + 2);
-            v = f32x4{a.x, a.y, b.x, b.y};
-        } else {
-            v = f32x4{p[0], p[1], p[2], p[3]};
-        }
+        const f32x4_a4* p = reinterpret_cast<const f32x4_a4*>(static_cast<const float*>(series) + e);
+        return STREAM ? __builtin_nontemporal_load(p) : *p;
     } else {
-        const uint16_t* p = static_cast<const uint16_t*>(series) + e;
-        if constexpr (ALIGN_CLASS == 0) {
-            u32x2 w = *reinterpret_cast<const u32x2*>(p);
-            v = f32x4{widen_bf16_lo(w.x), widen_bf16_hi(w.x), widen_bf16_lo(w.y), widen_bf16_hi(w.y)};
-        } else if constexpr (ALIGN_CLASS == 2) {
-            uint32_t a = *reinterpret_cast<const uint32_t*>(p);
-            uint32_t b = *reinterpret_cast<const uint32_t*>(p + 2);
-            v = f32x4{widen_bf16_lo(a), widen_bf16_hi(a), widen_bf16_lo(b), widen_bf16_hi(b)};
-        } else {
-            v = f32x4{widen_bf16_lo(p[0]), widen_bf16_lo(p[1]), widen_bf16_lo(p[2]), widen_bf16_lo(p[3])};
-        }
+        const u32x2_a2* p = reinterpret_cast<const u32x2_a2*>(static_cast<const uint16_t*>(series) + e);
+        const u32x2_a2 w = STREAM ? __builtin_nontemporal_load(p) : *p;
+        return f32x4{widen_bf16_lo(w.x), widen_bf16_hi(w.x), widen_bf16_lo(w.y), widen_bf16_hi(w.y)};
     }
-    return v;
 }
 
 // (v - mean[f]) / std[f] for the four elements of quad q.  FSTATIC in {1, 2, 4}: the feature of
@@ -111,50 +96,24 @@ __device__ __forceinline__ f32x4 standardise_quad(f32x4 v, uint32_t q, const Gat
     return r;
 }
 
-// grid = (ceil(units_total / (kThreads*UNROLL)), count).  Workgroup (bx, j) handles quads
-// [bx*kThreads*UNROLL, ...) of sample j; consecutive lanes take consecutive quads, so every load
-// and store instruction of a wave covers 1 KiB of contiguous memory.  All UNROLL loads are
-// issued before the first use to keep UNROLL*16 bytes per lane in flight.
-template <int STORE_BYTES, int FSTATIC, int UNROLL>
-__global__ void __launch_bounds__(kThreads) gather_quads_kernel(GatherArgs a) {
+// grid = (ceil(units_total / THREADS), count): workgroup (bx, j) handles THREADS consecutive
+// quads of sample j, one quad per lane, so each load and each store instruction of a wave covers
+// 1 KiB of contiguous memory.  One quad per lane with many resident waves measured faster on
+// MI355X than deeper per-lane unrolling (more, shorter waves keep both the read and the write
+// stream busy); the division costs nothing at this rate.
+template <int STORE_BYTES, int FSTATIC, int THREADS, bool STREAM>
+__global__ void __launch_bounds__(THREADS) gather_quads_kernel(GatherArgs a) {
     const uint32_t j = blockIdx.y;
+    const uint32_t q = blockIdx.x * THREADS + threadIdx.x;
+    if (q >= a.units_total) return;
     const int64_t e0 = span_offset(a, j);
-    const uint32_t q0 = blockIdx.x * (kThreads * UNROLL) + threadIdx.x;
-    const uint32_t align = static_cast<uint32_t>(e0) & 3u;  // uniform over the workgroup
-
-    f32x4 v[UNROLL];
-    if (align == 0) {
-#pragma unroll
-        for (int u = 0; u < UNROLL; ++u) {
-            uint32_t q = q0 + u * kThreads;
-            if (q < a.units_total) v[u] = load_quad<STORE_BYTES, 0>(a.series, e0 + 4ll * q);
-        }
-    } else if (align == 2) {
-#pragma unroll
-        for (int u = 0; u < UNROLL; ++u) {
-            uint32_t q = q0 + u * kThreads;
-            if (q < a.units_total) v[u] = load_quad<STORE_BYTES, 2>(a.series, e0 + 4ll * q);
-        }
-    } else {
-#pragma unroll
-        for (int u = 0; u < UNROLL; ++u) {
-            uint32_t q = q0 + u * kThreads;
-            if (q < a.units_total) v[u] = load_quad<STORE_BYTES, 1>(a.series, e0 + 4ll * q);
-        }
-    }
-
-    f32x4* x_base = reinterpret_cast<f32x4*>(a.out_x) + static_cast<size_t>(j) * a.units_x;
-    f32x4* y_base = reinterpret_cast<f32x4*>(a.out_y) +
-                    static_cast<size_t>(j) * (a.units_total - a.units_x);
-#pragma unroll
-    for (int u = 0; u < UNROLL; ++u) {
-        uint32_t q = q0 + u * kThreads;
-        if (q < a.units_total) {
-            f32x4 r = standardise_quad<FSTATIC>(v[u], q, a);
-            f32x4* dst = (q < a.units_x) ? (x_base + q) : (y_base + (q - a.units_x));
-            __builtin_nontemporal_store(r, dst);  // written once, never re-read by this kernel
-        }
-    }
+    const f32x4 v = load_quad<STORE_BYTES, STREAM>(a.series, e0 + 4ll * q);
+    const f32x4 r = standardise_quad<FSTATIC>(v, q, a);
+    f32x4* dst = (q < a.units_x)
+                     ? reinterpret_cast<f32x4*>(a.out_x) + static_cast<size_t>(j) * a.units_x + q
+                     : reinterpret_cast<f32x4*>(a.out_y) +
+                           static_cast<size_t>(j) * (a.units_total - a.units_x) + (q - a.units_x);
+    __builtin_nontemporal_store(r, dst);  // written once, never re-read by this kernel
 }
 
 // Any geometry (P*R or Q*R not a multiple of 4): one element per thread.
@@ -179,24 +138,29 @@ __global__ void __launch_bounds__(kThreads) gather_scalar_kernel(GatherArgs a) {
 }
 
 template <int STORE_BYTES, int FSTATIC>
-void launch_quads(const GatherArgs& a, int32_t count, hipStream_t s) {
-    // Large samples: 8 quads (128 B) per lane in flight.  Small samples: 1 quad per lane so that
-    // a sample still spreads over several workgroups.
-    if (a.units_total >= 8u * kThreads * 8u) {
-        dim3 grid((a.units_total + kThreads * 8 - 1) / (kThreads * 8), count);
-        hipLaunchKernelGGL((gather_quads_kernel<STORE_BYTES, FSTATIC, 8>), grid, dim3(kThreads), 0, s, a);
+void launch_quads(const GatherArgs& a, int32_t count, bool stream_loads, hipStream_t s) {
+    // 512-lane workgroups for long samples (fewer workgroups to dispatch), 256 otherwise.
+    if (a.units_total >= 32768u) {
+        dim3 grid((a.units_total + 511) / 512, count);
+        if (stream_loads)
+            hipLaunchKernelGGL((gather_quads_kernel<STORE_BYTES, FSTATIC, 512, true>), grid, dim3(512), 0, s, a);
+        else
+            hipLaunchKernelGGL((gather_quads_kernel<STORE_BYTES, FSTATIC, 512, false>), grid, dim3(512), 0, s, a);
     } else {
-        dim3 grid((a.units_total + kThreads - 1) / kThreads, count);
-        hipLaunchKernelGGL((gather_quads_kernel<STORE_BYTES, FSTATIC, 1>), grid, dim3(kThreads), 0, s, a);
+        dim3 grid((a.units_total + 255) / 256, count);
+        if (stream_loads)
+            hipLaunchKernelGGL((gather_quads_kernel<STORE_BYTES, FSTATIC, 256, true>), grid, dim3(256), 0, s, a);
+        else
+            hipLaunchKernelGGL((gather_quads_kernel<STORE_BYTES, FSTATIC, 256, false>), grid, dim3(256), 0, s, a);
     }
 }
 
 template <int STORE_BYTES>
-void launch_quads_f(const GatherArgs& a, int32_t count, hipStream_t s) {
-    if (a.F == 1) launch_quads<STORE_BYTES, 1>(a, count, s);
-    else if (a.F == 2) launch_quads<STORE_BYTES, 2>(a, count, s);
-    else if (a.F == 4) launch_quads<STORE_BYTES, 4>(a, count, s);
-    else launch_quads<STORE_BYTES, 0>(a, count, s);
+void launch_quads_f(const GatherArgs& a, int32_t count, bool stream_loads, hipStream_t s) {
+    if (a.F == 1) launch_quads<STORE_BYTES, 1>(a, count, stream_loads, s);
+    else if (a.F == 2) launch_quads<STORE_BYTES, 2>(a, count, stream_loads, s);
+    else if (a.F == 4) launch_quads<STORE_BYTES, 4>(a, count, stream_loads, s);
+    else launch_quads<STORE_BYTES, 0>(a, count, stream_loads, s);
 }
 
 }  // namespace
@@ -221,8 +185,10 @@ hipError_t launch_batch_gather(const pgti_ctx* c, const int32_t* d_starts, int32
     if (c->path == GatherPath::kQuads) {
         a.units_x = static_cast<uint32_t>(ex / 4);
         a.units_total = static_cast<uint32_t>(et / 4);
-        if (c->storage == PGTI_F32) launch_quads_f<4>(a, count, s);
-        else launch_quads_f<2>(a, count, s);
+        // Non-temporal loads once the series cannot live in the 256 MB last-level cache anyway.
+        const bool stream_loads = c->series_bytes > (256ull << 20);
+        if (c->storage == PGTI_F32) launch_quads_f<4>(a, count, stream_loads, s);
+        else launch_quads_f<2>(a, count, stream_loads, s);
     } else {
         a.units_x = static_cast<uint32_t>(ex);
         a.units_total = static_cast<uint32_t>(et);
