@@ -34,6 +34,11 @@ def parse_args():
                     help="output buffer pairs rotated (0 = enough to exceed the 256 MB last-level cache)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-batches", type=int, default=0, help="oracle batches on one core (0 = auto)")
+    ap.add_argument("--roofline-launches", type=int, default=4096,
+                    help="upper bound on back-to-back launches in the kernel-duration measurement")
+    ap.add_argument("--copy-calibration", type=int, default=3,
+                    help="plain device copies of one x buffer issued after the measurements: a kernel of "
+                         "known traffic for scaling rocprofv3's FETCH_SIZE / WRITE_SIZE counters")
     return ap.parse_args()
 
 
@@ -174,8 +179,8 @@ def main():
     ctx.epoch_indices(w.seed, w.epochs[0], w.rank, w.world)
     ctx.get_indices()  # waits for the sort so that only gather launches sit between the events
     full = nb - 1 if n_share % w.B else nb  # full batches only: every launch moves the same bytes
-    full = max(1, min(full, 4096))
-    reps = max(1, min(8, 4096 // full))
+    full = max(1, min(full, args.roofline_launches))
+    reps = max(1, min(8, args.roofline_launches // full))
     ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     for b in range(min(full, 32)):
         ctx.build_batch_raw(b, xp[b % pairs], yp[b % pairs], sh)
@@ -193,6 +198,11 @@ def main():
     avg_launch_s = ev0.elapsed_time(ev1) * 1e-3 / launches
     bytes_per_launch = bsz * w.bytes_per_snapshot()
     achieved = bytes_per_launch / avg_launch_s / 1e9
+
+    # ---- calibration copies for the counter runs (known size: reads and writes one x buffer) ----
+    for _ in range(args.copy_calibration):
+        xs[1].copy_(xs[0])
+    torch.cuda.synchronize()
 
     # ---- index generation alone ----------------------------------------------------------------
     torch.cuda.synchronize()
@@ -228,6 +238,8 @@ def main():
             "avg_launch_us": avg_launch_s * 1e6, "algorithmic_bytes_per_launch": bytes_per_launch,
         },
         "epoch_indices_ms": t_idx * 1e3,
+        "copy_calibration": {"count": args.copy_calibration, "bytes_read": xs[0].numel() * 4,
+                             "bytes_written": xs[0].numel() * 4},
         "setup": {"generate_s": t_gen, "load_with_device_stats_s": t_load, "load_s": t_load2,
                   "series_bytes": w.series_bytes_f32, "load_gb_per_s": w.series_bytes_f32 / t_load2 / 1e9},
     }
