@@ -30,8 +30,10 @@ def parse_args():
     ap.add_argument("--steps", type=int, default=0, help="batches to time (0 = one full epoch)")
     ap.add_argument("--warmup", type=int, default=64)
     ap.add_argument("--workload", default="statewide")
+    ap.add_argument("--batches-per-launch", type=int, default=0,
+                    help="batches built by one launch (0 = auto: about 512 MB of traffic per launch)")
     ap.add_argument("--out-pairs", type=int, default=0,
-                    help="output buffer pairs rotated (0 = enough to exceed the 256 MB last-level cache)")
+                    help="output buffer sets rotated (0 = enough to exceed the 256 MB last-level cache)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-batches", type=int, default=0, help="oracle batches on one core (0 = auto)")
     ap.add_argument("--roofline-launches", type=int, default=4096,
@@ -42,14 +44,19 @@ def parse_args():
     return ap.parse_args()
 
 
-def traffic_from_profiles(workload: str):
+def traffic_from_profiles(workload: str, batches_per_launch: int):
     """HBM bytes per launch measured with rocprofv3 --pmc (FETCH_SIZE / WRITE_SIZE, scaled by a
-    copy kernel of known size); recorded in profiles/ by hand after a counter run, else null."""
+    copy kernel of known size); recorded in profiles/ after a counter run of this same launch
+    shape, else null."""
     path = os.path.join(ROOT, "profiles", f"gather_{workload}_pmc.md")
     try:
+        found = {}
         for line in open(path):
-            if line.startswith("traffic_bytes_per_launch:"):
-                return float(line.split(":", 1)[1].split()[0])
+            for key in ("traffic_bytes_per_launch", "batches_per_launch"):
+                if line.startswith(key + ":"):
+                    found[key] = float(line.split(":", 1)[1].split()[0])
+        if found.get("batches_per_launch", 1) == batches_per_launch:
+            return found.get("traffic_bytes_per_launch")
     except OSError:
         pass
     return None
@@ -140,68 +147,93 @@ def main():
     ctx.load_series(host, w.P, w.Q, w.B, storage, mean, std)
     t_load2 = time.perf_counter() - t0
 
-    # ---- output buffers: rotate enough pairs that writes cannot sit in the last-level cache ----
-    out_bytes = w.B * (w.P + w.Q) * w.N * w.F * 4
-    pairs = args.out_pairs or max(4, -(-(512 << 20) // out_bytes))
-    pairs = min(pairs, 256)
-    xs = [torch.empty((w.B, w.P, w.N, w.F), dtype=torch.float32, device="cuda") for _ in range(pairs)]
-    ys = [torch.empty((w.B, w.Q, w.N, w.F), dtype=torch.float32, device="cuda") for _ in range(pairs)]
+    # ---- launch shape: k batches per launch (pgti_build_batches) -----------------------------------
+    n_share = ctx.epoch_indices(w.seed, w.epochs[0], w.rank, w.world)
+    nb = ctx.num_batches()
+    batch_bytes = w.B * w.bytes_per_snapshot()            # algorithmic read + write of a full batch
+    out_bytes = w.B * (w.P + w.Q) * w.N * w.F * 4         # x + y of one batch
+    k = args.batches_per_launch or max(1, min(nb, -(-(512 << 20) // batch_bytes)))
+    k = min(k, nb, 65535 // w.B)
+
+    # ---- output buffers: rotate enough sets that writes cannot sit in the 256 MB last-level cache --
+    sets = args.out_pairs or min(64, max(3, -(-(768 << 20) // (k * out_bytes))))
+    xs = [torch.empty((k, w.B, w.P, w.N, w.F), dtype=torch.float32, device="cuda") for _ in range(sets)]
+    ys = [torch.empty((k, w.B, w.Q, w.N, w.F), dtype=torch.float32, device="cuda") for _ in range(sets)]
     xp, yp = [t.data_ptr() for t in xs], [t.data_ptr() for t in ys]
     stream = torch.cuda.current_stream()
     sh = stream.cuda_stream
-
-    n_share = ctx.epoch_indices(w.seed, w.epochs[0], w.rank, w.world)
-    nb = ctx.num_batches()
     steps = args.steps or nb * len(w.epochs)
 
-    def run(n_steps: int, first_step: int = 0) -> int:
-        """Enqueues n_steps batches, generating indices at each epoch boundary.  Returns snapshots."""
-        snaps = 0
-        for i in range(first_step, first_step + n_steps):
+    x_batch_bytes, y_batch_bytes = w.B * w.P * w.N * w.F * 4, w.B * w.Q * w.N * w.F * 4
+
+    def out_ptrs(launch: int, per_launch: int):
+        """Rotates launches over every slot of every set (per_launch consecutive slots each)."""
+        per_set = max(1, k // per_launch)
+        idx = launch % (sets * per_set)
+        st, slot = divmod(idx, per_set)
+        return xp[st] + slot * per_launch * x_batch_bytes, yp[st] + slot * per_launch * y_batch_bytes
+
+    def run(n_steps: int, per_launch: int) -> int:
+        """Enqueues n_steps batches (per_launch of them per launch), generating the indices at each
+        epoch boundary.  Returns the number of snapshots built."""
+        snaps, i, launch = 0, 0, 0
+        while i < n_steps:
             e, b = divmod(i, nb)
             if b == 0:
                 ctx.epoch_indices(w.seed, w.epochs[0] + e, w.rank, w.world)  # consecutive epochs
-            rc = ctx.build_batch_raw(b, xp[i % pairs], yp[i % pairs], sh)
+            kk = min(per_launch, nb - b, n_steps - i)
+            rc = ctx.build_batches_raw(b, kk, *out_ptrs(launch, per_launch), sh)
             if rc < 0:
                 raise RuntimeError(pgti.last_error())
             snaps += rc
+            i += kk
+            launch += 1
         return snaps
 
-    # ---- warm-up, then the timed region --------------------------------------------------------
-    run(args.warmup)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    snaps = run(steps)
-    torch.cuda.synchronize()
-    elapsed = time.perf_counter() - t0
+    def timed(per_launch: int):
+        run(args.warmup, per_launch)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        n = run(steps, per_launch)
+        torch.cuda.synchronize()
+        return n, time.perf_counter() - t0
 
-    # ---- dominant kernel: batch builds back to back between two events on the launch stream -----
-    ctx.epoch_indices(w.seed, w.epochs[0], w.rank, w.world)
-    ctx.get_indices()  # waits for the sort so that only gather launches sit between the events
-    full = nb - 1 if n_share % w.B else nb  # full batches only: every launch moves the same bytes
-    full = max(1, min(full, args.roofline_launches))
-    reps = max(1, min(8, args.roofline_launches // full))
-    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    for b in range(min(full, 32)):
-        ctx.build_batch_raw(b, xp[b % pairs], yp[b % pairs], sh)
-    torch.cuda.synchronize()
-    ev0.record(stream)
-    k = 0
-    for _ in range(reps):
-        for b in range(full):
-            ctx.build_batch_raw(b, xp[k % pairs], yp[k % pairs], sh)
-            k += 1
-    ev1.record(stream)
-    torch.cuda.synchronize()
-    launches = reps * full
-    bsz = min(w.B, n_share)
-    avg_launch_s = ev0.elapsed_time(ev1) * 1e-3 / launches
-    bytes_per_launch = bsz * w.bytes_per_snapshot()
-    achieved = bytes_per_launch / avg_launch_s / 1e9
+    def kernel_rate(per_launch: int):
+        """Average duration of back-to-back launches of per_launch FULL batches, from HIP events on
+        the launch stream; only gather launches sit between the two events."""
+        ctx.epoch_indices(w.seed, w.epochs[0], w.rank, w.world)
+        ctx.get_indices()  # waits for the sort
+        full_batches = max(1, nb - 1 if n_share % w.B else nb)
+        per_launch = min(per_launch, full_batches)
+        per_epoch = max(1, full_batches // per_launch)
+        per_epoch = min(per_epoch, args.roofline_launches)
+        reps = max(1, min(64, args.roofline_launches // per_epoch))
+        ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        for l in range(min(per_epoch, 16)):
+            ctx.build_batches_raw(l * per_launch, per_launch, *out_ptrs(l, per_launch), sh)
+        torch.cuda.synchronize()
+        ev0.record(stream)
+        n = 0
+        for _ in range(reps):
+            for l in range(per_epoch):
+                ctx.build_batches_raw(l * per_launch, per_launch, *out_ptrs(n, per_launch), sh)
+                n += 1
+        ev1.record(stream)
+        torch.cuda.synchronize()
+        avg_s = ev0.elapsed_time(ev1) * 1e-3 / n
+        nbytes = per_launch * min(w.B, n_share) * w.bytes_per_snapshot()
+        return {"launches": n, "avg_launch_us": avg_s * 1e6, "algorithmic_bytes_per_launch": nbytes,
+                "achieved": nbytes / avg_s / 1e9, "batches_per_launch": per_launch}
+
+    # ---- warm-up, timed region, kernel rate: k batches per launch, then one batch per launch -------
+    snaps, elapsed = timed(k)
+    rate_k = kernel_rate(k)
+    snaps1, elapsed1 = timed(1) if k > 1 else (snaps, elapsed)
+    rate_1 = kernel_rate(1) if k > 1 else rate_k
 
     # ---- calibration copies for the counter runs (known size: reads and writes one x buffer) ----
     for _ in range(args.copy_calibration):
-        xs[1].copy_(xs[0])
+        xs[1][0].copy_(xs[0][0])
     torch.cuda.synchronize()
 
     # ---- index generation alone ----------------------------------------------------------------
@@ -228,18 +260,23 @@ def main():
         "config": {"workload": w.name, "T": w.T, "N": w.N, "F": w.F, "P": w.P, "Q": w.Q, "B": w.B,
                    "storage": w.storage, "world": w.world, "rank": w.rank, "seed": w.seed,
                    "epochs": list(w.epochs), "batches_per_epoch": nb, "snapshots_timed": snaps,
-                   "out_buffer_pairs": pairs},
+                   "batches_per_launch": k, "out_buffer_sets": sets},
         "gb_per_s": snaps * w.bytes_per_snapshot() / elapsed / 1e9,
         "pct_of_hbm_peak": snaps * w.bytes_per_snapshot() / elapsed / 1e9 / HBM_PEAK_GBS * 100,
         "roofline": {
-            "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-            "frac": achieved / HBM_PEAK_GBS, "traffic": traffic_from_profiles(w.name),
-            "kernel": "gather_quads_kernel", "launches": launches,
-            "avg_launch_us": avg_launch_s * 1e6, "algorithmic_bytes_per_launch": bytes_per_launch,
+            "bound": "hbm", "achieved": rate_k["achieved"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
+            "frac": rate_k["achieved"] / HBM_PEAK_GBS, "traffic": traffic_from_profiles(w.name, k),
+            "kernel": "gather_quads_kernel", **{kk: v for kk, v in rate_k.items() if kk != "achieved"},
+        },
+        "one_batch_per_launch": {
+            "value": snaps1 / elapsed1, "unit": "snapshots/s", "ms_per_step": elapsed1 / steps * 1e3,
+            "gb_per_s": snaps1 * w.bytes_per_snapshot() / elapsed1 / 1e9,
+            "roofline": {"achieved": rate_1["achieved"], "frac": rate_1["achieved"] / HBM_PEAK_GBS,
+                         **{kk: v for kk, v in rate_1.items() if kk != "achieved"}},
         },
         "epoch_indices_ms": t_idx * 1e3,
-        "copy_calibration": {"count": args.copy_calibration, "bytes_read": xs[0].numel() * 4,
-                             "bytes_written": xs[0].numel() * 4},
+        "copy_calibration": {"count": args.copy_calibration, "bytes_read": xs[0][0].numel() * 4,
+                             "bytes_written": xs[0][0].numel() * 4},
         "setup": {"generate_s": t_gen, "load_with_device_stats_s": t_load, "load_s": t_load2,
                   "series_bytes": w.series_bytes_f32, "load_gb_per_s": w.series_bytes_f32 / t_load2 / 1e9},
     }

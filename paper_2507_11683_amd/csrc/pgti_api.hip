@@ -406,8 +406,8 @@ int64_t pgti_num_batches(pgti_ctx* c) {
     return (len + c->B - 1) / c->B;
 }
 
-int pgti_build_batch(pgti_ctx* c, int64_t batch_no, float* out_x, float* out_y, void* stream) {
-    g_error[0] = 0;
+// Common part of the single- and multi-batch builds: checks, stream ordering, launches.
+static int64_t build_range(pgti_ctx* c, int64_t first_batch, int64_t k, float* out_x, float* out_y, void* stream) {
     if (!c) return fail(PGTI_ERR_ARG, "null context");
     if (!c->loaded) return fail(PGTI_ERR_STATE, "no series loaded");
     if (!c->have_share) return fail(PGTI_ERR_STATE, "no epoch indices generated");
@@ -416,10 +416,13 @@ int pgti_build_batch(pgti_ctx* c, int64_t batch_no, float* out_x, float* out_y, 
         return fail(PGTI_ERR_ARG, "outputs must be 16-byte aligned");
     const int64_t len = c->share_hi - c->share_lo;
     const int64_t nb = (len + c->B - 1) / c->B;
-    if (batch_no < 0 || batch_no >= nb)
-        return fail(PGTI_ERR_RANGE, "batch %lld not in [0, %lld)", (long long)batch_no, (long long)nb);
-    const int64_t first = batch_no * c->B;
-    const int32_t count = static_cast<int32_t>((len - first < c->B) ? (len - first) : c->B);
+    if (k < 1) return fail(PGTI_ERR_RANGE, "batch count %lld must be at least 1", (long long)k);
+    if (first_batch < 0 || first_batch >= nb || k > nb - first_batch)
+        return fail(PGTI_ERR_RANGE, "batches [%lld, %lld) not in [0, %lld)", (long long)first_batch,
+                    (long long)(first_batch + k), (long long)nb);
+    const int64_t first = first_batch * c->B;
+    const int64_t last = (first + k * c->B < len) ? (first + k * c->B) : len;
+    const int64_t count = last - first;
 
     DeviceGuard guard(c->device);
     if (guard.status != hipSuccess) return fail_hip(guard.status, "hipSetDevice");
@@ -427,7 +430,7 @@ int pgti_build_batch(pgti_ctx* c, int64_t batch_no, float* out_x, float* out_y, 
 
     // First build on this stream since the last sort: make the stream wait for the share.
     bool known = false;
-    for (int k = 0; k < c->n_tracked; ++k) known = known || (c->tracked[k].stream == s);
+    for (int t = 0; t < c->n_tracked; ++t) known = known || (c->tracked[t].stream == s);
     if (!known) {
         int slot = c->n_tracked;
         if (c->n_tracked == kMaxTrackedStreams) {
@@ -441,8 +444,26 @@ int pgti_build_batch(pgti_ctx* c, int64_t batch_no, float* out_x, float* out_y, 
         c->tracked[slot].stream = s;
     }
 
-    PGTI_HIP_TRY(launch_batch_gather(c, c->d_share + first, count, out_x, out_y, s));
+    // Samples are consecutive in the share and in the outputs, so several batches are one launch
+    // with more samples; the grid's sample dimension holds at most 65,535.
+    const int64_t x_stride = static_cast<int64_t>(c->P) * c->R, y_stride = static_cast<int64_t>(c->Q) * c->R;
+    for (int64_t done = 0; done < count; done += 65535) {
+        const int32_t part = static_cast<int32_t>((count - done < 65535) ? (count - done) : 65535);
+        PGTI_HIP_TRY(launch_batch_gather(c, c->d_share + first + done, part, out_x + done * x_stride,
+                                         out_y + done * y_stride, s));
+    }
     return count;
+}
+
+int pgti_build_batch(pgti_ctx* c, int64_t batch_no, float* out_x, float* out_y, void* stream) {
+    g_error[0] = 0;
+    return static_cast<int>(build_range(c, batch_no, 1, out_x, out_y, stream));
+}
+
+int64_t pgti_build_batches(pgti_ctx* c, int64_t first_batch, int32_t k, float* out_x, float* out_y,
+                           void* stream) {
+    g_error[0] = 0;
+    return build_range(c, first_batch, k, out_x, out_y, stream);
 }
 
 const char* pgti_last_error(void) { return g_error; }

@@ -285,6 +285,70 @@ def test_batches_follow_new_epoch_without_host_sync():
 
 
 # ----------------------------------------------------------------------------------------------
+# several batches per launch
+# ----------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("storage_name", ["f32", "bf16"])
+def test_multi_batch_launch_matches_oracle_and_single_launches(storage_name):
+    w = workloads.WORKLOADS["tiny"]
+    series = workloads.make_series(w)
+    mean, std = oracle.series_stats(series)
+    storage = pgti.PGTI_F32 if storage_name == "f32" else pgti.PGTI_BF16
+    ser_o = _oracle_series(series, storage)
+    canary = -777.0
+    with pgti.Context(0) as ctx:
+        ctx.load_series(series, w.P, w.Q, w.B, storage, mean, std)
+        n_share = ctx.epoch_indices(3, 2)
+        share = ctx.get_indices()
+        nb = ctx.num_batches()
+        for first, k in [(0, 1), (3, 5), (0, nb), (nb - 2, 2), (nb - 1, 1)]:
+            x = torch.full((k, w.B, w.P, w.N, w.F), canary, dtype=torch.float32, device="cuda")
+            y = torch.full((k, w.B, w.Q, w.N, w.F), canary, dtype=torch.float32, device="cuda")
+            total = ctx.build_batches(first, k, x, y)
+            torch.cuda.synchronize()
+            starts = share[first * w.B:(first + k) * w.B]
+            assert total == len(starts)
+            wx, wy = oracle.build_batch(ser_o, storage, w.P, w.Q, mean, std, starts)
+            gx = x.cpu().numpy().reshape(k * w.B, w.P, w.N, w.F)
+            gy = y.cpu().numpy().reshape(k * w.B, w.Q, w.N, w.F)
+            assert _bits_equal(gx[:total], wx) and _bits_equal(gy[:total], wy), (first, k)
+            assert np.all(gx[total:] == canary) and np.all(gy[total:] == canary)
+            # slot i of the multi-batch output == what the single-batch call writes for batch first+i
+            x1, y1 = _alloc_out(w.B, w.P, w.Q, w.N, w.F)
+            for i in (0, k - 1):
+                cnt = ctx.build_batch(first + i, x1, y1)
+                torch.cuda.synchronize()
+                assert torch.equal(x1[:cnt].view(torch.int32), x[i, :cnt].view(torch.int32))
+                assert torch.equal(y1[:cnt].view(torch.int32), y[i, :cnt].view(torch.int32))
+        x, y = _alloc_out(w.B, w.P, w.Q, w.N, w.F)
+        for first, k in [(0, 0), (0, nb + 1), (nb, 1), (-1, 1), (nb - 1, 2)]:
+            rc = ctx.build_batches_raw(first, k, x.data_ptr(), y.data_ptr(), 0)
+            assert rc == pgti.PGTI_ERR_RANGE, (first, k, rc)
+
+
+def test_multi_batch_statewide_sampled(statewide_series):
+    # the launch shape the benchmark times: 4 batches of 32 per launch at full size
+    w = workloads.WORKLOADS["statewide"]
+    mean, std = _sampled_stats(statewide_series)
+    k = 4
+    with pgti.Context(0) as ctx:
+        ctx.load_series(statewide_series, w.P, w.Q, w.B, pgti.PGTI_F32, mean, std)
+        ctx.epoch_indices(w.seed, 0)
+        share = ctx.get_indices()
+        nb = ctx.num_batches()
+        x = torch.empty((k, w.B, w.P, w.N, w.F), dtype=torch.float32, device="cuda")
+        y = torch.empty((k, w.B, w.Q, w.N, w.F), dtype=torch.float32, device="cuda")
+        for first in (0, 1640, nb - k):
+            total = ctx.build_batches(first, k, x, y)
+            torch.cuda.synchronize()
+            starts = share[first * w.B:(first + k) * w.B]
+            assert total == len(starts)
+            wx, wy = oracle.build_batch(statewide_series, oracle.F32, w.P, w.Q, mean, std, starts)
+            gx = x.cpu().numpy().reshape(k * w.B, w.P, w.N, w.F)[:total]
+            gy = y.cpu().numpy().reshape(k * w.B, w.Q, w.N, w.F)[:total]
+            assert _bits_equal(gx, wx) and _bits_equal(gy, wy), first
+
+
+# ----------------------------------------------------------------------------------------------
 # statistics computed by the library
 # ----------------------------------------------------------------------------------------------
 @pytest.mark.parametrize("storage_name", ["f32", "bf16"])
