@@ -9,9 +9,20 @@
 // no contraction, so no MFMA and no LDS (with shuffled starts two samples of a batch almost never
 // share a row, so there is nothing to stage).
 //
-// Bit exactness: (v - mean[f]) / std[f] is one IEEE binary32 subtraction and one correctly
-// rounded binary32 division (the compiler's default expansion; this file is built with
-// -ffp-contract=off and without fast-math, fp32 denormals on).
+// Bit exactness: (v - mean[f]) / std[f] is one IEEE binary32 subtraction followed by a correctly
+// rounded binary32 division.  The division has two implementations with identical results:
+//   * the compiler's expansion of `/` (this file is built with -ffp-contract=off, no fast-math,
+//     fp32 denormals on), used whenever a guard fails;
+//   * a fast path: the divisor is one of F constants, so its reciprocal r = RN(1/sigma) is
+//     computed once on the host (in fp64, rounded once), and q0 = d*r is corrected twice with
+//     the exact residual, e = fma(-sigma, q, d); q = fma(e, r, q).  The second correction applied
+//     to a faithful quotient with a correctly rounded reciprocal yields RN(d/sigma) (Markstein's
+//     theorem) as long as nothing overflows or underflows, which the guards ensure: sigma's
+//     biased exponent in [95, 159], d's in [63, 191] (this also sends zeros, subnormals,
+//     infinities and NaNs to the `/` path).  6 full-rate VALU operations per element instead of
+//     about 15 issue slots; it matters when the stored type is bf16 (+7 % bandwidth) and is
+//     hidden behind memory time for fp32.  tests/fastdiv_model.c checks the identity on the host
+//     for every guarded dividend of hard divisors and for random divisors.
 #include "pgti_internal.h"
 
 namespace pgti {
@@ -35,8 +46,10 @@ struct GatherArgs {
     uint32_t F;
     float mean[kInlineStats];
     float stdev[kInlineStats];
-    const float* d_mean;  // used when F > kInlineStats
+    float recip[kInlineStats];  // RN(1 / stdev[f]), meaningful on the fast-division path only
+    const float* d_mean;        // used when F is not 1, 2 or 4
     const float* d_std;
+    const float* d_recip;
 };
 
 __device__ __forceinline__ float widen_bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
@@ -67,33 +80,65 @@ __device__ __forceinline__ f32x4 load_quad(const void* series, int64_t e) {
     }
 }
 
+// d / sigma, correctly rounded.  FAST: reciprocal multiply plus two exact-residual corrections when
+// d's exponent is in the guarded range, the ordinary division otherwise (see the file header).
+__device__ __forceinline__ bool dividend_in_range(float d) {
+    return ((__float_as_uint(d) & 0x7FFFFFFFu) - (63u << 23)) < (129u << 23);
+}
+
+__device__ __forceinline__ float corrected_quotient(float d, float sigma, float r) {
+    const float q0 = d * r;
+    const float e0 = __builtin_fmaf(-sigma, q0, d);
+    const float q1 = __builtin_fmaf(e0, r, q0);
+    const float e1 = __builtin_fmaf(-sigma, q1, d);
+    return __builtin_fmaf(e1, r, q1);
+}
+
 // (v - mean[f]) / std[f] for the four elements of quad q.  FSTATIC in {1, 2, 4}: the feature of
 // lane k of a quad does not depend on q (every span starts on a row, so on feature 0);
 // FSTATIC == 0: any F, the feature is ((4q + k) mod F).
-template <int FSTATIC>
+template <int FSTATIC, bool FAST>
 __device__ __forceinline__ f32x4 standardise_quad(f32x4 v, uint32_t q, const GatherArgs& a) {
-    f32x4 m, s;
+    f32x4 m, s, r;
     if constexpr (FSTATIC == 1) {
         m = f32x4{a.mean[0], a.mean[0], a.mean[0], a.mean[0]};
         s = f32x4{a.stdev[0], a.stdev[0], a.stdev[0], a.stdev[0]};
+        r = f32x4{a.recip[0], a.recip[0], a.recip[0], a.recip[0]};
     } else if constexpr (FSTATIC == 2) {
         m = f32x4{a.mean[0], a.mean[1], a.mean[0], a.mean[1]};
         s = f32x4{a.stdev[0], a.stdev[1], a.stdev[0], a.stdev[1]};
+        r = f32x4{a.recip[0], a.recip[1], a.recip[0], a.recip[1]};
     } else if constexpr (FSTATIC == 4) {
         m = f32x4{a.mean[0], a.mean[1], a.mean[2], a.mean[3]};
         s = f32x4{a.stdev[0], a.stdev[1], a.stdev[2], a.stdev[3]};
+        r = f32x4{a.recip[0], a.recip[1], a.recip[2], a.recip[3]};
     } else {
         uint32_t f0 = static_cast<uint32_t>((4ull * q) % a.F);
         uint32_t f1 = (f0 + 1) % a.F, f2 = (f0 + 2) % a.F, f3 = (f0 + 3) % a.F;
         m = f32x4{a.d_mean[f0], a.d_mean[f1], a.d_mean[f2], a.d_mean[f3]};
         s = f32x4{a.d_std[f0], a.d_std[f1], a.d_std[f2], a.d_std[f3]};
+        if constexpr (FAST) r = f32x4{a.d_recip[f0], a.d_recip[f1], a.d_recip[f2], a.d_recip[f3]};
     }
-    f32x4 r;
-    r.x = (v.x - m.x) / s.x;
-    r.y = (v.y - m.y) / s.y;
-    r.z = (v.z - m.z) / s.z;
-    r.w = (v.w - m.w) / s.w;
-    return r;
+    const f32x4 d = f32x4{v.x - m.x, v.y - m.y, v.z - m.z, v.w - m.w};
+    f32x4 o;
+    if constexpr (FAST) {
+        const bool all_in_range = static_cast<bool>(static_cast<int>(dividend_in_range(d.x)) &
+                                                    static_cast<int>(dividend_in_range(d.y)) &
+                                                    static_cast<int>(dividend_in_range(d.z)) &
+                                                    static_cast<int>(dividend_in_range(d.w)));
+        if (all_in_range) {
+            o.x = corrected_quotient(d.x, s.x, r.x);
+            o.y = corrected_quotient(d.y, s.y, r.y);
+            o.z = corrected_quotient(d.z, s.z, r.z);
+            o.w = corrected_quotient(d.w, s.w, r.w);
+            return o;
+        }
+    }
+    o.x = d.x / s.x;
+    o.y = d.y / s.y;
+    o.z = d.z / s.z;
+    o.w = d.w / s.w;
+    return o;
 }
 
 // grid = (ceil(units_total / THREADS), count): workgroup (bx, j) handles THREADS consecutive
@@ -101,14 +146,14 @@ __device__ __forceinline__ f32x4 standardise_quad(f32x4 v, uint32_t q, const Gat
 // 1 KiB of contiguous memory.  One quad per lane with many resident waves measured faster on
 // MI355X than deeper per-lane unrolling (more, shorter waves keep both the read and the write
 // stream busy); the division costs nothing at this rate.
-template <int STORE_BYTES, int FSTATIC, int THREADS, bool STREAM>
+template <int STORE_BYTES, int FSTATIC, int THREADS, bool STREAM, bool FAST>
 __global__ void __launch_bounds__(THREADS) gather_quads_kernel(GatherArgs a) {
     const uint32_t j = blockIdx.y;
     const uint32_t q = blockIdx.x * THREADS + threadIdx.x;
     if (q >= a.units_total) return;
     const int64_t e0 = span_offset(a, j);
     const f32x4 v = load_quad<STORE_BYTES, STREAM>(a.series, e0 + 4ll * q);
-    const f32x4 r = standardise_quad<FSTATIC>(v, q, a);
+    const f32x4 r = standardise_quad<FSTATIC, FAST>(v, q, a);
     f32x4* dst = (q < a.units_x)
                      ? reinterpret_cast<f32x4*>(a.out_x) + static_cast<size_t>(j) * a.units_x + q
                      : reinterpret_cast<f32x4*>(a.out_y) +
@@ -137,30 +182,31 @@ __global__ void __launch_bounds__(kThreads) gather_scalar_kernel(GatherArgs a) {
     *dst = r;
 }
 
-template <int STORE_BYTES, int FSTATIC>
-void launch_quads(const GatherArgs& a, int32_t count, bool stream_loads, hipStream_t s) {
-    // 512-lane workgroups for long samples (fewer workgroups to dispatch), 256 otherwise.
-    if (a.units_total >= 32768u) {
-        dim3 grid((a.units_total + 511) / 512, count);
-        if (stream_loads)
-            hipLaunchKernelGGL((gather_quads_kernel<STORE_BYTES, FSTATIC, 512, true>), grid, dim3(512), 0, s, a);
-        else
-            hipLaunchKernelGGL((gather_quads_kernel<STORE_BYTES, FSTATIC, 512, false>), grid, dim3(512), 0, s, a);
+template <int STORE_BYTES, int FSTATIC, int THREADS>
+void launch_quads_t(const GatherArgs& a, int32_t count, bool stream_loads, bool fast, hipStream_t s) {
+    dim3 grid((a.units_total + THREADS - 1) / THREADS, count), block(THREADS);
+    if (stream_loads) {
+        if (fast) hipLaunchKernelGGL((gather_quads_kernel<STORE_BYTES, FSTATIC, THREADS, true, true>), grid, block, 0, s, a);
+        else hipLaunchKernelGGL((gather_quads_kernel<STORE_BYTES, FSTATIC, THREADS, true, false>), grid, block, 0, s, a);
     } else {
-        dim3 grid((a.units_total + 255) / 256, count);
-        if (stream_loads)
-            hipLaunchKernelGGL((gather_quads_kernel<STORE_BYTES, FSTATIC, 256, true>), grid, dim3(256), 0, s, a);
-        else
-            hipLaunchKernelGGL((gather_quads_kernel<STORE_BYTES, FSTATIC, 256, false>), grid, dim3(256), 0, s, a);
+        if (fast) hipLaunchKernelGGL((gather_quads_kernel<STORE_BYTES, FSTATIC, THREADS, false, true>), grid, block, 0, s, a);
+        else hipLaunchKernelGGL((gather_quads_kernel<STORE_BYTES, FSTATIC, THREADS, false, false>), grid, block, 0, s, a);
     }
 }
 
+template <int STORE_BYTES, int FSTATIC>
+void launch_quads(const GatherArgs& a, int32_t count, bool stream_loads, bool fast, hipStream_t s) {
+    // 512-lane workgroups for long samples (fewer workgroups to dispatch), 256 otherwise.
+    if (a.units_total >= 32768u) launch_quads_t<STORE_BYTES, FSTATIC, 512>(a, count, stream_loads, fast, s);
+    else launch_quads_t<STORE_BYTES, FSTATIC, 256>(a, count, stream_loads, fast, s);
+}
+
 template <int STORE_BYTES>
-void launch_quads_f(const GatherArgs& a, int32_t count, bool stream_loads, hipStream_t s) {
-    if (a.F == 1) launch_quads<STORE_BYTES, 1>(a, count, stream_loads, s);
-    else if (a.F == 2) launch_quads<STORE_BYTES, 2>(a, count, stream_loads, s);
-    else if (a.F == 4) launch_quads<STORE_BYTES, 4>(a, count, stream_loads, s);
-    else launch_quads<STORE_BYTES, 0>(a, count, stream_loads, s);
+void launch_quads_f(const GatherArgs& a, int32_t count, bool stream_loads, bool fast, hipStream_t s) {
+    if (a.F == 1) launch_quads<STORE_BYTES, 1>(a, count, stream_loads, fast, s);
+    else if (a.F == 2) launch_quads<STORE_BYTES, 2>(a, count, stream_loads, fast, s);
+    else if (a.F == 4) launch_quads<STORE_BYTES, 4>(a, count, stream_loads, fast, s);
+    else launch_quads<STORE_BYTES, 0>(a, count, stream_loads, fast, s);
 }
 
 }  // namespace
@@ -178,17 +224,19 @@ hipError_t launch_batch_gather(const pgti_ctx* c, const int32_t* d_starts, int32
     for (int f = 0; f < kInlineStats && f < c->F; ++f) {
         a.mean[f] = c->mean[f];
         a.stdev[f] = c->stdev[f];
+        a.recip[f] = c->recip[f];
     }
     a.d_mean = c->d_stats;
     a.d_std = c->d_stats + c->F;
+    a.d_recip = c->d_stats + 2 * c->F;
     const int64_t ex = static_cast<int64_t>(c->P) * c->R, et = static_cast<int64_t>(c->P + c->Q) * c->R;
     if (c->path == GatherPath::kQuads) {
         a.units_x = static_cast<uint32_t>(ex / 4);
         a.units_total = static_cast<uint32_t>(et / 4);
         // Non-temporal loads once the series cannot live in the 256 MB last-level cache anyway.
         const bool stream_loads = c->series_bytes > (256ull << 20);
-        if (c->storage == PGTI_F32) launch_quads_f<4>(a, count, stream_loads, s);
-        else launch_quads_f<2>(a, count, stream_loads, s);
+        if (c->storage == PGTI_F32) launch_quads_f<4>(a, count, stream_loads, c->fast_divide, s);
+        else launch_quads_f<2>(a, count, stream_loads, c->fast_divide, s);
     } else {
         a.units_x = static_cast<uint32_t>(ex);
         a.units_total = static_cast<uint32_t>(et);

@@ -144,7 +144,7 @@ int load_impl(pgti_ctx* c, const float* src, bool src_on_device, int64_t T, int3
 
     const uint32_t nblk = static_cast<uint32_t>((n + kSortTile - 1) / kSortTile);
     if (int rc = alloc(&c->d_series, elems * store_bytes)) return rc;
-    if (int rc = alloc(&c->d_stats, sizeof(float) * 2 * F)) return rc;
+    if (int rc = alloc(&c->d_stats, sizeof(float) * 3 * F)) return rc;
     if (int rc = alloc(&c->d_keys[0], sizeof(uint64_t) * n)) return rc;
     if (int rc = alloc(&c->d_keys[1], sizeof(uint64_t) * n)) return rc;
     if (int rc = alloc(&c->d_vals[0], sizeof(int32_t) * n)) return rc;
@@ -251,6 +251,20 @@ int load_impl(pgti_ctx* c, const float* src, bool src_on_device, int64_t T, int3
         PGTI_HIP_TRY(hipMemcpy(c->d_stats, c->mean.data(), sizeof(float) * F, hipMemcpyHostToDevice));
         PGTI_HIP_TRY(hipMemcpy(c->d_stats + F, c->stdev.data(), sizeof(float) * F, hipMemcpyHostToDevice));
     }
+
+    // Reciprocals for the gather's fast division: 1/sigma in fp64 rounded once to fp32 is the
+    // correctly rounded fp32 reciprocal (53 >= 2*24 + 2 bits).  The fast path needs every sigma's
+    // biased exponent in [95, 159]; otherwise the kernels divide the ordinary way.
+    c->recip.assign(F, 1.0f);
+    c->fast_divide = true;
+    for (int32_t f = 0; f < F; ++f) {
+        uint32_t bits;
+        memcpy(&bits, &c->stdev[f], 4);
+        const uint32_t expo = (bits >> 23) & 0xFFu;
+        if (expo < 95u || expo > 159u) c->fast_divide = false;
+        c->recip[f] = static_cast<float>(1.0 / static_cast<double>(c->stdev[f]));
+    }
+    PGTI_HIP_TRY(hipMemcpy(c->d_stats + 2 * F, c->recip.data(), sizeof(float) * F, hipMemcpyHostToDevice));
 
     c->T = T;
     c->N = N;

@@ -45,7 +45,9 @@ struct pgti_ctx {
     void* d_series = nullptr;
     size_t series_bytes = 0;
     std::vector<float> mean, stdev;  // host copies, F entries
-    float* d_stats = nullptr;        // device: mean[F] then std[F]
+    std::vector<float> recip;        // RN(1 / stdev[f]) for the gather's fast division
+    bool fast_divide = false;        // every stdev[f] inside the range the fast division is valid for
+    float* d_stats = nullptr;        // device: mean[F], std[F], recip[F]
     pgti::GatherPath path = pgti::GatherPath::kScalar;
 
     // epoch index generation

@@ -197,6 +197,28 @@ def test_geometry_sweep(geom, storage_name):
             _check_batches(ctx, ser_o, storage, P, Q, B, mean, std, share, range(ctx.num_batches()))
 
 
+@pytest.mark.parametrize("std", [(8.9, 1.0), (1.9999999, 0.33333334), (-7.25, 1.0000001),
+                                 (1e-12, 3e10), (2.3283064e-10, 4294967040.0), (1e-30, 1e30)])
+@pytest.mark.parametrize("storage_name", ["f32", "bf16"])
+def test_division_over_random_bit_patterns(std, storage_name):
+    # Dividends of every magnitude class (normal of all exponents, subnormal, zero, Inf, NaN) against
+    # divisors inside the range of the kernel's reciprocal-based division, at its edges, and outside
+    # it (where the kernel must divide the ordinary way).  Every result must be RN((v - mu) / sigma).
+    rng = np.random.default_rng(int(abs(std[0]) * 1000) % 9973 + (storage_name == "bf16"))
+    T, N, F, P, Q, B = 40, 2048, 2, 4, 4, 16
+    bits = rng.integers(0, 2 ** 32, size=(T, N, F), dtype=np.uint64).astype(np.uint32)
+    series = bits.view(np.float32)
+    mean = np.array([0.0, 1.5], np.float32)
+    stdv = np.array(std, np.float32)
+    storage = pgti.PGTI_F32 if storage_name == "f32" else pgti.PGTI_BF16
+    with pgti.Context(0) as ctx:
+        ctx.load_series(series, P, Q, B, storage, mean, stdv)
+        ctx.epoch_indices(11, 0)
+        share = ctx.get_indices()
+        _check_batches(ctx, _oracle_series(series, storage), storage, P, Q, B, mean, stdv, share,
+                       range(ctx.num_batches()))
+
+
 def test_identity_channel_returns_stored_bits():
     # mean 0 / std 1 on every feature: outputs are exactly the stored values (for bf16 storage,
     # the oracle's rounded bits widened), which checks the resident store itself.
