@@ -82,8 +82,17 @@ __device__ __forceinline__ f32x4 load_quad(const void* series, int64_t e) {
 
 // d / sigma, correctly rounded.  FAST: reciprocal multiply plus two exact-residual corrections when
 // d's exponent is in the guarded range, the ordinary division otherwise (see the file header).
-__device__ __forceinline__ bool dividend_in_range(float d) {
-    return ((__float_as_uint(d) & 0x7FFFFFFFu) - (63u << 23)) < (129u << 23);
+__device__ __forceinline__ uint32_t magnitude_bits(float d) { return __float_as_uint(d) & 0x7FFFFFFFu; }
+
+// True when all four dividends have a biased exponent in [63, 191]: the smallest and the largest
+// magnitude bit pattern bound all four (NaN and Inf patterns are the largest, zero and subnormals
+// the smallest).
+__device__ __forceinline__ bool dividends_in_range(f32x4 d) {
+    const uint32_t a = magnitude_bits(d.x), b = magnitude_bits(d.y), c = magnitude_bits(d.z),
+                   e = magnitude_bits(d.w);
+    const uint32_t lo = min(min(a, b), min(c, e));
+    const uint32_t hi = max(max(a, b), max(c, e));
+    return static_cast<bool>(static_cast<int>(lo >= (63u << 23)) & static_cast<int>(hi < (192u << 23)));
 }
 
 __device__ __forceinline__ float corrected_quotient(float d, float sigma, float r) {
@@ -94,50 +103,73 @@ __device__ __forceinline__ float corrected_quotient(float d, float sigma, float 
     return __builtin_fmaf(e1, r, q1);
 }
 
-// (v - mean[f]) / std[f] for the four elements of quad q.  FSTATIC in {1, 2, 4}: the feature of
-// lane k of a quad does not depend on q (every span starts on a row, so on feature 0);
-// FSTATIC == 0: any F, the feature is ((4q + k) mod F).
-template <int FSTATIC, bool FAST>
-__device__ __forceinline__ f32x4 standardise_quad(f32x4 v, uint32_t q, const GatherArgs& a) {
+// Per-quad constants: mean, std and reciprocal of the feature of each of the four elements.
+struct QuadStats {
     f32x4 m, s, r;
+};
+
+// FSTATIC in {1, 2, 4}: the feature of element k of a quad does not depend on q (every span
+// starts on a row, so on feature 0) and the constants come straight from the argument block;
+// FSTATIC == 0: any F, the feature is ((4q + k) mod F) and the constants are read from memory.
+template <int FSTATIC, bool FAST>
+__device__ __forceinline__ QuadStats quad_stats(uint32_t q, const GatherArgs& a) {
+    QuadStats t;
+    t.r = f32x4{1.f, 1.f, 1.f, 1.f};
     if constexpr (FSTATIC == 1) {
-        m = f32x4{a.mean[0], a.mean[0], a.mean[0], a.mean[0]};
-        s = f32x4{a.stdev[0], a.stdev[0], a.stdev[0], a.stdev[0]};
-        r = f32x4{a.recip[0], a.recip[0], a.recip[0], a.recip[0]};
+        t.m = f32x4{a.mean[0], a.mean[0], a.mean[0], a.mean[0]};
+        t.s = f32x4{a.stdev[0], a.stdev[0], a.stdev[0], a.stdev[0]};
+        if constexpr (FAST) t.r = f32x4{a.recip[0], a.recip[0], a.recip[0], a.recip[0]};
     } else if constexpr (FSTATIC == 2) {
-        m = f32x4{a.mean[0], a.mean[1], a.mean[0], a.mean[1]};
-        s = f32x4{a.stdev[0], a.stdev[1], a.stdev[0], a.stdev[1]};
-        r = f32x4{a.recip[0], a.recip[1], a.recip[0], a.recip[1]};
+        t.m = f32x4{a.mean[0], a.mean[1], a.mean[0], a.mean[1]};
+        t.s = f32x4{a.stdev[0], a.stdev[1], a.stdev[0], a.stdev[1]};
+        if constexpr (FAST) t.r = f32x4{a.recip[0], a.recip[1], a.recip[0], a.recip[1]};
     } else if constexpr (FSTATIC == 4) {
-        m = f32x4{a.mean[0], a.mean[1], a.mean[2], a.mean[3]};
-        s = f32x4{a.stdev[0], a.stdev[1], a.stdev[2], a.stdev[3]};
-        r = f32x4{a.recip[0], a.recip[1], a.recip[2], a.recip[3]};
+        t.m = f32x4{a.mean[0], a.mean[1], a.mean[2], a.mean[3]};
+        t.s = f32x4{a.stdev[0], a.stdev[1], a.stdev[2], a.stdev[3]};
+        if constexpr (FAST) t.r = f32x4{a.recip[0], a.recip[1], a.recip[2], a.recip[3]};
     } else {
         uint32_t f0 = static_cast<uint32_t>((4ull * q) % a.F);
         uint32_t f1 = (f0 + 1) % a.F, f2 = (f0 + 2) % a.F, f3 = (f0 + 3) % a.F;
-        m = f32x4{a.d_mean[f0], a.d_mean[f1], a.d_mean[f2], a.d_mean[f3]};
-        s = f32x4{a.d_std[f0], a.d_std[f1], a.d_std[f2], a.d_std[f3]};
-        if constexpr (FAST) r = f32x4{a.d_recip[f0], a.d_recip[f1], a.d_recip[f2], a.d_recip[f3]};
+        t.m = f32x4{a.d_mean[f0], a.d_mean[f1], a.d_mean[f2], a.d_mean[f3]};
+        t.s = f32x4{a.d_std[f0], a.d_std[f1], a.d_std[f2], a.d_std[f3]};
+        if constexpr (FAST) t.r = f32x4{a.d_recip[f0], a.d_recip[f1], a.d_recip[f2], a.d_recip[f3]};
     }
-    const f32x4 d = f32x4{v.x - m.x, v.y - m.y, v.z - m.z, v.w - m.w};
+    return t;
+}
+
+// Keeps the argument-block constants live in scalar registers from this point on, so that their
+// (scalar) loads are issued together at the top of the kernel instead of one by one after the data
+// has arrived: a wave only lives for one quad, so every serialised load latency costs bandwidth.
+template <int FSTATIC>
+__device__ __forceinline__ void pin_uniform(const QuadStats& t) {
+    if constexpr (FSTATIC == 1) {
+        asm volatile("" ::"s"(t.m.x), "s"(t.s.x), "s"(t.r.x));
+    } else if constexpr (FSTATIC == 2) {
+        asm volatile("" ::"s"(t.m.x), "s"(t.s.x), "s"(t.r.x), "s"(t.m.y), "s"(t.s.y), "s"(t.r.y));
+    } else if constexpr (FSTATIC == 4) {
+        asm volatile("" ::"s"(t.m.x), "s"(t.s.x), "s"(t.r.x), "s"(t.m.y), "s"(t.s.y), "s"(t.r.y));
+        asm volatile("" ::"s"(t.m.z), "s"(t.s.z), "s"(t.r.z), "s"(t.m.w), "s"(t.s.w), "s"(t.r.w));
+    }
+}
+
+// (v - mean[f]) / std[f] for the four elements of a quad.
+template <bool FAST>
+__device__ __forceinline__ f32x4 standardise_quad(f32x4 v, const QuadStats& t) {
+    const f32x4 d = f32x4{v.x - t.m.x, v.y - t.m.y, v.z - t.m.z, v.w - t.m.w};
     f32x4 o;
     if constexpr (FAST) {
-        const bool all_in_range = static_cast<bool>(static_cast<int>(dividend_in_range(d.x)) &
-                                                    static_cast<int>(dividend_in_range(d.y)) &
-                                                    static_cast<int>(dividend_in_range(d.z)) &
-                                                    static_cast<int>(dividend_in_range(d.w)));
-        if (all_in_range) {
-            o.x = corrected_quotient(d.x, s.x, r.x);
-            o.y = corrected_quotient(d.y, s.y, r.y);
-            o.z = corrected_quotient(d.z, s.z, r.z);
-            o.w = corrected_quotient(d.w, s.w, r.w);
+        if (dividends_in_range(d)) {
+            o.x = corrected_quotient(d.x, t.s.x, t.r.x);
+            o.y = corrected_quotient(d.y, t.s.y, t.r.y);
+            o.z = corrected_quotient(d.z, t.s.z, t.r.z);
+            o.w = corrected_quotient(d.w, t.s.w, t.r.w);
             return o;
         }
     }
-    o.x = d.x / s.x;
-    o.y = d.y / s.y;
-    o.z = d.z / s.z;
-    o.w = d.w / s.w;
+    o.x = d.x / t.s.x;
+    o.y = d.y / t.s.y;
+    o.z = d.z / t.s.z;
+    o.w = d.w / t.s.w;
     return o;
 }
 
@@ -150,10 +182,14 @@ template <int STORE_BYTES, int FSTATIC, int THREADS, bool STREAM, bool FAST>
 __global__ void __launch_bounds__(THREADS) gather_quads_kernel(GatherArgs a) {
     const uint32_t j = blockIdx.y;
     const uint32_t q = blockIdx.x * THREADS + threadIdx.x;
-    if (q >= a.units_total) return;
+    // The start is read before the pin below: an asm statement counts as a possible memory clobber,
+    // after which this uniform read would no longer be done by the scalar unit.
     const int64_t e0 = span_offset(a, j);
+    const QuadStats t = quad_stats<FSTATIC, FAST>(q, a);
+    pin_uniform<FSTATIC>(t);
+    if (q >= a.units_total) return;
     const f32x4 v = load_quad<STORE_BYTES, STREAM>(a.series, e0 + 4ll * q);
-    const f32x4 r = standardise_quad<FSTATIC, FAST>(v, q, a);
+    const f32x4 r = standardise_quad<FAST>(v, t);
     f32x4* dst = (q < a.units_x)
                      ? reinterpret_cast<f32x4*>(a.out_x) + static_cast<size_t>(j) * a.units_x + q
                      : reinterpret_cast<f32x4*>(a.out_y) +
