@@ -58,6 +58,9 @@ def _load():
         lib.oracle_sort_pairs.argtypes = [vp, i64, vp]
         lib.oracle_epoch_perm.restype = ctypes.c_int
         lib.oracle_epoch_perm.argtypes = [u64, u64, i64, vp]
+        lib.oracle_epoch_indices_ex.restype = ctypes.c_int
+        lib.oracle_epoch_indices_ex.argtypes = [ctypes.c_int, i64, i64, i64, i64, u64, u64, i64, i64, vp,
+                                                ctypes.POINTER(i64)]
         lib.oracle_rank_share.restype = ctypes.c_int
         lib.oracle_rank_share.argtypes = [i64, i64, i64, ctypes.POINTER(i64), ctypes.POINTER(i64)]
         lib.oracle_bf16_from_f32.restype = ctypes.c_uint16
@@ -150,6 +153,20 @@ def epoch_indices(seed: int, epoch: int, rank: int, world: int, n: int) -> np.nd
     """One rank's share of the epoch: perm[lo:hi)."""
     lo, hi = rank_share(n, rank, world)
     return epoch_perm(seed, epoch, n)[lo:hi].copy()
+
+
+ORDER_SHUFFLE, ORDER_SEQUENTIAL, ORDER_BATCH_SHUFFLE = 0, 1, 2
+
+
+def epoch_indices_ex(order: int, n_windows: int, first_start: int, n_starts: int, B: int, seed: int,
+                     epoch: int, rank: int = 0, world: int = 1) -> np.ndarray:
+    """One rank's share for any order (global shuffle / sequential / batch-level shuffle) over the
+    range of starts [first_start, first_start + n_starts)."""
+    out = np.empty(max(n_starts, 1), dtype=np.int32)
+    n = ctypes.c_int64()
+    _check(_load().oracle_epoch_indices_ex(order, n_windows, first_start, n_starts, B, seed, epoch, rank,
+                                           world, _ptr(out), ctypes.byref(n)), "epoch_indices_ex")
+    return out[:n.value].copy()
 
 
 def bf16_from_f32(v: float) -> int:

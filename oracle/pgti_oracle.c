@@ -141,6 +141,66 @@ int oracle_rank_share(int64_t n, int64_t rank, int64_t world, int64_t* lo, int64
 }
 
 /* ------------------------------------------------------------------------------------------
+ * Other epoch orders and start ranges.
+ *
+ * Range: Sec. 3.1 splits the windows 70/10/20 into train, validation and test, and Algorithm 1
+ * takes x_train as the leading part of the stacked windows, so a split is a contiguous range
+ * of starts [first_start, first_start + n_starts).  Positions inside the range are 0..n_starts-1.
+ *
+ * order 0, global shuffle (Sec. 4.2): positions sorted by (key(seed, epoch, position), position),
+ *          the rank takes its contiguous slice of that order.
+ * order 1, sequential (validation / test passes, and the unshuffled reading of Algorithm 1):
+ *          the rank takes its contiguous slice [lo, hi) of the positions in time order.
+ * order 2, batch-level shuffle (Sec. 5.4: a fixed data partition per worker; the order of the
+ *          batches is shuffled while the data inside a batch stays fixed): the rank's partition
+ *          is the same slice [lo, hi) as in order 1, every epoch; it is cut into consecutive
+ *          batches of B positions; the full batches are visited in the order of ascending
+ *          (key(seed, epoch, position of the batch's first element), batch number); a short
+ *          remainder batch, if any, comes last so that only the last batch of a share is short.
+ * Every returned value is first_start + position.
+ * ---------------------------------------------------------------------------------------- */
+int oracle_epoch_indices_ex(int order, int64_t n_windows, int64_t first_start, int64_t n_starts,
+                            int64_t B, uint64_t seed, uint64_t epoch, int64_t rank, int64_t world,
+                            int32_t* out, int64_t* n_out) {
+    if (!n_out || first_start < 0 || n_starts < 0 || first_start + n_starts > n_windows || B <= 0)
+        return ORACLE_ERR_ARG;
+    int64_t lo, hi;
+    if (oracle_rank_share(n_starts, rank, world, &lo, &hi) != ORACLE_OK) return ORACLE_ERR_ARG;
+    int64_t len = hi - lo;
+    *n_out = len;
+    if (len > 0 && !out) return ORACLE_ERR_ARG;
+    if (order == 0) {
+        int32_t* perm = (int32_t*)malloc((size_t)(n_starts > 0 ? n_starts : 1) * sizeof(int32_t));
+        if (!perm) return ORACLE_ERR_ARG;
+        int rc = oracle_epoch_perm(seed, epoch, n_starts, perm);
+        for (int64_t i = 0; rc == ORACLE_OK && i < len; ++i) out[i] = (int32_t)(first_start + perm[lo + i]);
+        free(perm);
+        return rc;
+    }
+    if (order == 1) {
+        for (int64_t i = 0; i < len; ++i) out[i] = (int32_t)(first_start + lo + i);
+        return ORACLE_OK;
+    }
+    if (order == 2) {
+        int64_t n_full = len / B;
+        uint64_t* keys = (uint64_t*)malloc((size_t)(n_full > 0 ? n_full : 1) * sizeof(uint64_t));
+        int32_t* batch_order = (int32_t*)malloc((size_t)(n_full > 0 ? n_full : 1) * sizeof(int32_t));
+        if (!keys || !batch_order) { free(keys); free(batch_order); return ORACLE_ERR_ARG; }
+        for (int64_t b = 0; b < n_full; ++b) keys[b] = oracle_key(seed, epoch, (uint64_t)(lo + b * B));
+        int rc = oracle_sort_pairs(keys, n_full, batch_order);
+        for (int64_t i = 0; rc == ORACLE_OK && i < n_full; ++i)
+            for (int64_t j = 0; j < B; ++j)
+                out[i * B + j] = (int32_t)(first_start + lo + (int64_t)batch_order[i] * B + j);
+        for (int64_t i = n_full * B; rc == ORACLE_OK && i < len; ++i) /* the short remainder batch */
+            out[i] = (int32_t)(first_start + lo + i);
+        free(keys);
+        free(batch_order);
+        return rc;
+    }
+    return ORACLE_ERR_ARG;
+}
+
+/* ------------------------------------------------------------------------------------------
  * Storage rounding (this build's bf16 store; the paper has none).
  * fp32 -> bf16 keeps the upper 16 bits, rounding to nearest, ties to even.
  * ---------------------------------------------------------------------------------------- */

@@ -444,3 +444,77 @@ def test_fused_equals_prestandardised_then_sliced():
     for j, s in enumerate(starts):
         assert np.array_equal(x[j].view(np.uint32), pre[s:s + P].view(np.uint32))
         assert np.array_equal(y[j].view(np.uint32), pre[s + P:s + P + Q].view(np.uint32))
+
+
+# ----------------------------------------------------------------------------------------------
+# other epoch orders and start ranges (Sec. 3.1 split, Sec. 5.4 batch-level shuffle)
+# ----------------------------------------------------------------------------------------------
+def _split_ranges(n):
+    n_train = round(n * 0.7)
+    n_val = round(n * 0.1)
+    return [(0, n_train), (n_train, n_val), (n_train + n_val, n - n_train - n_val)]
+
+
+def test_full_range_shuffle_is_the_plain_epoch_order():
+    n = 1977
+    for r, w in [(0, 1), (2, 5)]:
+        a = oracle.epoch_indices_ex(oracle.ORDER_SHUFFLE, n, 0, n, 64, 3, 4, r, w)
+        assert np.array_equal(a, oracle.epoch_indices(3, 4, r, w, n))
+
+
+def test_sequential_and_split_ranges_cover_every_start_once():
+    n = 34249
+    ranges = _split_ranges(n)
+    assert sum(c for _, c in ranges) == n and ranges[0][1] == 23974  # 70 % of the windows
+    seen = []
+    for first, count in ranges:
+        parts = [oracle.epoch_indices_ex(oracle.ORDER_SEQUENTIAL, n, first, count, 64, 0, 0, r, 3) for r in range(3)]
+        joined = np.concatenate(parts)
+        assert np.array_equal(joined, np.arange(first, first + count))
+        seen.append(joined)
+    assert np.array_equal(np.concatenate(seen), np.arange(n))
+    # shuffled order over a range: a permutation of exactly that range
+    first, count = ranges[1]
+    sh = oracle.epoch_indices_ex(oracle.ORDER_SHUFFLE, n, first, count, 64, 5, 1)
+    assert np.array_equal(np.sort(sh), np.arange(first, first + count))
+    assert np.array_equal(sh, first + oracle.epoch_perm(5, 1, count))
+    with pytest.raises(ValueError):
+        oracle.epoch_indices_ex(oracle.ORDER_SEQUENTIAL, n, n - 5, 6, 64, 0, 0)
+
+
+@pytest.mark.parametrize("count,B,world", [(1977, 64, 1), (6569, 32, 4), (100, 7, 3), (64, 64, 1), (63, 64, 1)])
+def test_batch_level_shuffle_keeps_batches_and_permutes_their_order(count, B, world):
+    n, first = count + 50, 13
+    orders = {}
+    for epoch in (0, 1):
+        shares = []
+        for r in range(world):
+            lo, hi = oracle.rank_share(count, r, world)
+            sh = oracle.epoch_indices_ex(oracle.ORDER_BATCH_SHUFFLE, n, first, count, B, 9, epoch, r, world)
+            assert len(sh) == hi - lo
+            # the worker's partition is fixed: the same contiguous slice of starts every epoch
+            assert np.array_equal(np.sort(sh), np.arange(first + lo, first + hi))
+            n_full = (hi - lo) // B
+            batches = sh[:n_full * B].reshape(n_full, B)
+            # data inside a batch stays fixed: B consecutive starts beginning on a batch boundary
+            assert np.all(np.diff(batches, axis=1) == 1)
+            assert np.all((batches[:, 0] - first - lo) % B == 0)
+            # the short remainder stays last
+            assert np.array_equal(sh[n_full * B:], np.arange(first + lo + n_full * B, first + hi))
+            # the order of the batches is the argsort of their keys (library argsort)
+            keys = np.array([oracle.key(9, epoch, lo + b * B) for b in range(n_full)], dtype=np.uint64)
+            assert np.array_equal((batches[:, 0] - first - lo) // B, np.argsort(keys, kind="stable"))
+            shares.append(sh)
+        orders[epoch] = shares
+    if count // world // B >= 8:
+        assert any(not np.array_equal(a, b) for a, b in zip(orders[0], orders[1]))  # reshuffled per epoch
+
+
+def test_consecutive_starts_share_rows():
+    # a batch of B consecutive starts touches B + P + Q - 1 distinct rows while emitting B*(P+Q)
+    B, P, Q = 32, 12, 12
+    starts = np.arange(1000, 1000 + B)
+    rows = set()
+    for s in starts:
+        rows.update(range(s, s + P + Q))
+    assert len(rows) == B + P + Q - 1
