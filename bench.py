@@ -34,6 +34,8 @@ def parse_args():
                     help="batches built by one launch (0 = auto: about 512 MB of traffic per launch)")
     ap.add_argument("--out-pairs", type=int, default=0,
                     help="output buffer sets rotated (0 = enough to exceed the 256 MB last-level cache)")
+    ap.add_argument("--order", default="shuffle", choices=["shuffle", "sequential", "batch_shuffle"],
+                    help="epoch order (the headline metric is the global shuffle)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-batches", type=int, default=0, help="oracle batches on one core (0 = auto)")
     ap.add_argument("--roofline-launches", type=int, default=4096,
@@ -62,7 +64,7 @@ def traffic_from_profiles(workload: str, batches_per_launch: int):
     return None
 
 
-def cpu_baseline(w, series, mean, std, n_batches_1core: int):
+def cpu_baseline(w, series, mean, std, n_batches_1core: int, order: int = 0):
     """The oracle as it stands, on this host, on a bounded sample of the same workload."""
     import concurrent.futures as cf
 
@@ -72,7 +74,7 @@ def cpu_baseline(w, series, mean, std, n_batches_1core: int):
 
     storage = oracle.F32 if w.storage == "f32" else oracle.BF16
     ser = series if storage == oracle.F32 else oracle.store_bf16(series)
-    share = oracle.epoch_indices(w.seed, w.epochs[0], w.rank, w.world, w.n_windows)
+    share = oracle.epoch_indices_ex(order, w.n_windows, 0, w.n_windows, w.B, w.seed, w.epochs[0], w.rank, w.world)
     nb = -(-len(share) // w.B)
     per_batch = lambda b: oracle.build_batch(ser, storage, w.P, w.Q, mean, std, share[b * w.B:(b + 1) * w.B])
     per_batch(0)  # touch code and pages once
@@ -148,11 +150,19 @@ def main():
     t_load2 = time.perf_counter() - t0
 
     # ---- launch shape: k batches per launch (pgti_build_batches) -----------------------------------
-    n_share = ctx.epoch_indices(w.seed, w.epochs[0], w.rank, w.world)
+    order = {"shuffle": pgti.PGTI_ORDER_SHUFFLE, "sequential": pgti.PGTI_ORDER_SEQUENTIAL,
+             "batch_shuffle": pgti.PGTI_ORDER_BATCH_SHUFFLE}[args.order]
+
+    def gen_indices(epoch: int) -> int:
+        return ctx.epoch_indices_ex(order, seed=w.seed, epoch=epoch, rank=w.rank, world=w.world)
+
+    n_share = gen_indices(w.epochs[0])
     nb = ctx.num_batches()
     batch_bytes = w.B * w.bytes_per_snapshot()            # algorithmic read + write of a full batch
     out_bytes = w.B * (w.P + w.Q) * w.N * w.F * 4         # x + y of one batch
     k = args.batches_per_launch or max(1, min(nb, -(-(512 << 20) // batch_bytes)))
+    if not args.batches_per_launch and args.order != "shuffle" and w.series_bytes_f32 > (256 << 20):
+        k = 1  # consecutive starts, write-bound row-centric kernel: measured fastest at one batch per launch
     k = min(k, nb, 65535 // w.B)
 
     # ---- output buffers: rotate enough sets that writes cannot sit in the 256 MB last-level cache --
@@ -180,7 +190,7 @@ def main():
         while i < n_steps:
             e, b = divmod(i, nb)
             if b == 0:
-                ctx.epoch_indices(w.seed, w.epochs[0] + e, w.rank, w.world)  # consecutive epochs
+                gen_indices(w.epochs[0] + e)  # consecutive epochs
             kk = min(per_launch, nb - b, n_steps - i)
             rc = ctx.build_batches_raw(b, kk, *out_ptrs(launch, per_launch), sh)
             if rc < 0:
@@ -201,7 +211,7 @@ def main():
     def kernel_rate(per_launch: int):
         """Average duration of back-to-back launches of per_launch FULL batches, from HIP events on
         the launch stream; only gather launches sit between the two events."""
-        ctx.epoch_indices(w.seed, w.epochs[0], w.rank, w.world)
+        gen_indices(w.epochs[0])
         ctx.get_indices()  # waits for the sort
         full_batches = max(1, nb - 1 if n_share % w.B else nb)
         per_launch = min(per_launch, full_batches)
@@ -240,7 +250,7 @@ def main():
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for e in range(10):
-        ctx.epoch_indices(w.seed, 100 + e, w.rank, w.world)
+        gen_indices(100 + e)
     ctx.get_indices()
     t_idx = (time.perf_counter() - t0) / 10
 
@@ -260,7 +270,7 @@ def main():
         "config": {"workload": w.name, "T": w.T, "N": w.N, "F": w.F, "P": w.P, "Q": w.Q, "B": w.B,
                    "storage": w.storage, "world": w.world, "rank": w.rank, "seed": w.seed,
                    "epochs": list(w.epochs), "batches_per_epoch": nb, "snapshots_timed": snaps,
-                   "batches_per_launch": k, "out_buffer_sets": sets},
+                   "batches_per_launch": k, "out_buffer_sets": sets, "order": args.order},
         "gb_per_s": snaps * w.bytes_per_snapshot() / elapsed / 1e9,
         "pct_of_hbm_peak": snaps * w.bytes_per_snapshot() / elapsed / 1e9 / HBM_PEAK_GBS * 100,
         "roofline": {
@@ -268,6 +278,12 @@ def main():
             "frac": rate_k["achieved"] / HBM_PEAK_GBS, "traffic": traffic_from_profiles(w.name, k),
             "kernel": "gather_quads_kernel", **{kk: v for kk, v in rate_k.items() if kk != "achieved"},
         },
+        # bytes a launch must move if every distinct source row is fetched once: equals the algorithmic
+        # bytes for the global shuffle (no shared rows), far fewer reads for consecutive starts
+        "unique_bytes_ideal_per_launch": (
+            rate_k["algorithmic_bytes_per_launch"] if args.order == "shuffle" else
+            (rate_k["batches_per_launch"] * w.B + w.P + w.Q - 1) * w.N * w.F * (4 if w.storage == "f32" else 2)
+            + rate_k["batches_per_launch"] * w.B * (w.P + w.Q) * w.N * w.F * 4),
         "one_batch_per_launch": {
             "value": snaps1 / elapsed1, "unit": "snapshots/s", "ms_per_step": elapsed1 / steps * 1e3,
             "gb_per_s": snaps1 * w.bytes_per_snapshot() / elapsed1 / 1e9,
@@ -283,7 +299,7 @@ def main():
     ctx.destroy()
     del xs, ys
     if not args.no_cpu_baseline:
-        result["cpu_baseline"] = cpu_baseline(w, series, mean, std, args.cpu_batches)
+        result["cpu_baseline"] = cpu_baseline(w, series, mean, std, args.cpu_batches, order)
     print(json.dumps(result))
 
 

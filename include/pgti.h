@@ -100,6 +100,48 @@ int pgti_get_stats(pgti_ctx* c, float* mean_out, float* std_out);
 int pgti_epoch_indices(pgti_ctx* c, uint64_t seed, uint64_t epoch, uint32_t rank, uint32_t world,
                        int64_t* n_share);
 
+/*
+ * Epoch index generation with an order and a range of starts.
+ *
+ * Range (Sec. 3.1: the windows are split 70/10/20 into train, validation and test; Algorithm 1
+ * takes the training part as the leading windows): the epoch runs over the starts
+ * [first_start, first_start + n_starts); n_starts < 0 means "to the last window".  Positions
+ * inside the range are 0..n_starts-1 and rank `rank` of `world` owns the positions
+ * [lo, hi) = [floor(rank*n_starts/world), floor((rank+1)*n_starts/world)) of the chosen order.
+ *
+ * order
+ *   PGTI_ORDER_SHUFFLE        Sec. 4.2 global shuffle: positions sorted by (key(seed, epoch,
+ *                             position), position); what pgti_epoch_indices does over all windows.
+ *   PGTI_ORDER_SEQUENTIAL     time order (validation and test passes): the share is
+ *                             first_start+lo .. first_start+hi-1.  seed and epoch are ignored.
+ *   PGTI_ORDER_BATCH_SHUFFLE  Sec. 5.4: a fixed partition per worker, the order of the batches is
+ *                             shuffled while the data inside a batch stays fixed.  The partition is
+ *                             the sequential share [lo, hi), every epoch; it is cut into consecutive
+ *                             batches of B positions; full batches are visited by ascending
+ *                             (key(seed, epoch, position of the batch's first element), batch
+ *                             number); a short remainder batch stays last.
+ * A batch of B consecutive starts reads only B+P+Q-1 distinct rows for B*(P+Q) written ones.
+ * Errors: ARG (null, unknown order), STATE, RANGE (rank/world, range outside the windows), HIP.
+ */
+typedef enum {
+    PGTI_ORDER_SHUFFLE = 0,
+    PGTI_ORDER_SEQUENTIAL = 1,
+    PGTI_ORDER_BATCH_SHUFFLE = 2
+} pgti_order;
+
+typedef struct pgti_epoch_spec {
+    int32_t order;       /* a pgti_order */
+    int32_t reserved;    /* set to 0 */
+    int64_t first_start; /* first start of the range */
+    int64_t n_starts;    /* number of starts in the range; negative = all remaining windows */
+    uint64_t seed;
+    uint64_t epoch;
+    uint32_t rank;
+    uint32_t world;
+} pgti_epoch_spec;
+
+int pgti_epoch_indices_ex(pgti_ctx* c, const pgti_epoch_spec* spec, int64_t* n_share);
+
 /* Test hook: copies the current share to host_out (HOST, int32, room for `capacity` entries).
  * Blocks until the sort has finished.  Returns the share length, or ERR_ARG if it does not fit. */
 int64_t pgti_get_indices(pgti_ctx* c, int32_t* host_out, int64_t capacity);

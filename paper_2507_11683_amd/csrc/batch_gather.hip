@@ -197,6 +197,53 @@ __global__ void __launch_bounds__(THREADS) gather_quads_kernel(GatherArgs a) {
     __builtin_nontemporal_store(r, dst);  // written once, never re-read by this kernel
 }
 
+// Row-centric variant for batches of CONSECUTIVE starts (sequential and batch-level-shuffled
+// orders): a batch of B' starts s0 .. s0+B'-1 touches only the B'+P+Q-1 source rows
+// s0 .. s0+B'+P+Q-2, but each interior row appears in P+Q different (sample, step) slots.
+// grid = (ceil(row_quads / THREADS), B+P+Q-1, batches): workgroup (bx, rr, b) loads one chunk of
+// source row s0_b + rr ONCE, standardises it once, and stores it to every slot that references
+// it: sample j = rr - p for each step p in [0, P+Q) with 0 <= j < B'.  HBM reads drop from
+// B'*(P+Q) rows to B'+P+Q-1 rows per batch and the arithmetic by the same factor; the kernel is
+// bound by the write stream alone.  Needs rows that start on a quad boundary (R % 4 == 0).
+struct RowArgs {
+    GatherArgs g;          // units_x / units_total are unused here
+    uint32_t B;            // batch size: samples per run
+    uint32_t count;        // samples in this launch (the last run may be short)
+    uint32_t P, PQ;        // input steps, P + Q
+    uint32_t row_quads;    // R / 4
+};
+
+template <int STORE_BYTES, int FSTATIC, int THREADS, bool STREAM, bool FAST>
+__global__ void __launch_bounds__(THREADS) gather_rows_kernel(RowArgs a) {
+    const uint32_t run = blockIdx.z, rr = blockIdx.y;
+    const uint32_t q = blockIdx.x * THREADS + threadIdx.x;  // quad inside the row
+    const uint32_t first_sample = run * a.B;
+    const uint32_t run_len = min(a.B, a.count - first_sample);
+    // First start of the run, clamped so that every row of the run lies inside the series.
+    int32_t s0 = a.g.starts[first_sample];
+    const int32_t s0_max = a.g.last_start - static_cast<int32_t>(run_len - 1);
+    s0 = s0 < 0 ? 0 : (s0 > s0_max ? s0_max : s0);
+    const QuadStats t = quad_stats<FSTATIC, FAST>(q, a.g);
+    pin_uniform<FSTATIC>(t);
+    if (rr >= run_len + a.PQ - 1 || q >= a.row_quads) return;
+
+    const int64_t e = (static_cast<int64_t>(s0) + rr) * a.g.R + 4ll * q;
+    const f32x4 r = standardise_quad<FAST>(load_quad<STORE_BYTES, STREAM>(a.g.series, e), t);
+
+    const uint32_t j_lo = (rr >= a.PQ - 1) ? rr - (a.PQ - 1) : 0u;
+    const uint32_t j_hi = (rr < run_len - 1) ? rr : run_len - 1;
+    f32x4* const x = reinterpret_cast<f32x4*>(a.g.out_x);
+    f32x4* const y = reinterpret_cast<f32x4*>(a.g.out_y);
+    const uint32_t Q = a.PQ - a.P;
+    for (uint32_t j = j_lo; j <= j_hi; ++j) {
+        const uint32_t p = rr - j;  // step of sample j that shows this row
+        const size_t sample = first_sample + j;
+        f32x4* dst = (p < a.P) ? x + (sample * a.P + p) * a.row_quads + q
+                               : y + (sample * Q + (p - a.P)) * a.row_quads + q;
+        __builtin_nontemporal_store(r, dst);
+    }
+}
+
 // Any geometry (P*R or Q*R not a multiple of 4): one element per thread.
 template <int STORE_BYTES>
 __global__ void __launch_bounds__(kThreads) gather_scalar_kernel(GatherArgs a) {
@@ -245,6 +292,28 @@ void launch_quads_f(const GatherArgs& a, int32_t count, bool stream_loads, bool 
     else launch_quads<STORE_BYTES, 0>(a, count, stream_loads, fast, s);
 }
 
+template <int STORE_BYTES, int FSTATIC>
+void launch_rows(const RowArgs& a, bool stream_loads, bool fast, hipStream_t s) {
+    constexpr int kT = 256;
+    const uint32_t runs = (a.count + a.B - 1) / a.B;
+    dim3 grid((a.row_quads + kT - 1) / kT, a.B + a.PQ - 1, runs), block(kT);
+    if (stream_loads) {
+        if (fast) hipLaunchKernelGGL((gather_rows_kernel<STORE_BYTES, FSTATIC, kT, true, true>), grid, block, 0, s, a);
+        else hipLaunchKernelGGL((gather_rows_kernel<STORE_BYTES, FSTATIC, kT, true, false>), grid, block, 0, s, a);
+    } else {
+        if (fast) hipLaunchKernelGGL((gather_rows_kernel<STORE_BYTES, FSTATIC, kT, false, true>), grid, block, 0, s, a);
+        else hipLaunchKernelGGL((gather_rows_kernel<STORE_BYTES, FSTATIC, kT, false, false>), grid, block, 0, s, a);
+    }
+}
+
+template <int STORE_BYTES>
+void launch_rows_f(const RowArgs& a, bool stream_loads, bool fast, hipStream_t s) {
+    if (a.g.F == 1) launch_rows<STORE_BYTES, 1>(a, stream_loads, fast, s);
+    else if (a.g.F == 2) launch_rows<STORE_BYTES, 2>(a, stream_loads, fast, s);
+    else if (a.g.F == 4) launch_rows<STORE_BYTES, 4>(a, stream_loads, fast, s);
+    else launch_rows<STORE_BYTES, 0>(a, stream_loads, fast, s);
+}
+
 }  // namespace
 
 hipError_t launch_batch_gather(const pgti_ctx* c, const int32_t* d_starts, int32_t count,
@@ -266,11 +335,25 @@ hipError_t launch_batch_gather(const pgti_ctx* c, const int32_t* d_starts, int32
     a.d_std = c->d_stats + c->F;
     a.d_recip = c->d_stats + 2 * c->F;
     const int64_t ex = static_cast<int64_t>(c->P) * c->R, et = static_cast<int64_t>(c->P + c->Q) * c->R;
-    if (c->path == GatherPath::kQuads) {
+    const bool big_series = c->series_bytes > (256ull << 20);
+    if (c->share_consecutive && c->R % 4 == 0 && c->B + c->P + c->Q - 1 <= 65535 &&
+        (count + c->B - 1) / c->B <= 65535) {
+        // Batches of consecutive starts: fetch every source row once (d_starts is batch aligned).
+        RowArgs ra{};
+        ra.g = a;
+        ra.B = static_cast<uint32_t>(c->B);
+        ra.count = static_cast<uint32_t>(count);
+        ra.P = static_cast<uint32_t>(c->P);
+        ra.PQ = static_cast<uint32_t>(c->P + c->Q);
+        ra.row_quads = static_cast<uint32_t>(c->R / 4);
+        if (c->storage == PGTI_F32) launch_rows_f<4>(ra, big_series, c->fast_divide, s);
+        else launch_rows_f<2>(ra, big_series, c->fast_divide, s);
+    } else if (c->path == GatherPath::kQuads) {
         a.units_x = static_cast<uint32_t>(ex / 4);
         a.units_total = static_cast<uint32_t>(et / 4);
         // Non-temporal loads once the series cannot live in the 256 MB last-level cache anyway.
-        const bool stream_loads = c->series_bytes > (256ull << 20);
+        // (with consecutive starts the rows are re-read by neighbouring samples: keep them cached)
+        const bool stream_loads = big_series && !c->share_consecutive;
         if (c->storage == PGTI_F32) launch_quads_f<4>(a, count, stream_loads, c->fast_divide, s);
         else launch_quads_f<2>(a, count, stream_loads, c->fast_divide, s);
     } else {

@@ -15,6 +15,11 @@
 //             digit of every key into the count table of the destination tile (integer atomics,
 //             order independent), so no separate counting launch is needed.
 // The key generation launch also produces the counts of pass 0.
+//
+// Other orders reuse the same machinery: the sequential order (validation / test passes over a
+// range of starts, Sec. 3.1) is an iota; the batch-level shuffle of Sec. 5.4 (fixed partition,
+// batch order shuffled, batch contents fixed) sorts one key per full batch and expands the sorted
+// batch numbers into starts.
 #include "pgti_internal.h"
 
 namespace pgti {
@@ -52,9 +57,11 @@ __device__ __forceinline__ uint32_t block_inclusive_scan(uint32_t v, uint32_t* l
     return r;
 }
 
-// keys[i] for i < n; counts of the lowest digit per (digit, workgroup) into hist0[digit][wg].
+// keys[i] = key(seed, epoch, counter_base + i*counter_stride) for i < n; counts of the lowest digit
+// per (digit, workgroup) into hist0[digit][wg].
 __global__ void __launch_bounds__(kThreads) keygen_kernel(uint64_t seed, uint64_t epoch, uint32_t n,
-                                                          uint32_t nblk, uint64_t* keys,
+                                                          uint32_t nblk, uint64_t counter_base,
+                                                          uint64_t counter_stride, uint64_t* keys,
                                                           uint32_t* hist0) {
     __shared__ uint32_t counts[kRadix];
     const uint32_t tid = threadIdx.x, b = blockIdx.x;
@@ -66,7 +73,7 @@ __global__ void __launch_bounds__(kThreads) keygen_kernel(uint64_t seed, uint64_
     for (uint32_t it = 0; it < kItems; ++it) {
         uint32_t i = b * kSortTile + it * kThreads + tid;
         if (i < n) {
-            uint64_t k = mix64((h1 ^ static_cast<uint64_t>(i)) + kGamma);
+            uint64_t k = mix64((h1 ^ (counter_base + static_cast<uint64_t>(i) * counter_stride)) + kGamma);
             keys[i] = k;
             atomicAdd(&counts[k & 0xFFu], 1u);
         }
@@ -103,14 +110,15 @@ __global__ void __launch_bounds__(kThreads) scan_kernel(uint32_t* hist, uint32_t
 
 // Stable scatter of one tile by the digit at `shift`.
 // FIRST: values are the element positions themselves (no value array yet).
-// LAST : only the values whose destination falls in [lo, hi) are written, to share[pos - lo].
+// LAST : only the values whose destination falls in [lo, hi) are written, to share[pos - lo],
+//        with value_offset added (the first start of the range the positions refer to).
 template <bool FIRST, bool LAST>
 __global__ void __launch_bounds__(kThreads) scatter_kernel(
     const uint64_t* __restrict__ keys_in, const int32_t* __restrict__ vals_in,
     uint64_t* __restrict__ keys_out, int32_t* __restrict__ vals_out,
     const uint32_t* __restrict__ hist_scanned, const uint32_t* __restrict__ tot,
     uint32_t* __restrict__ hist_next, uint32_t n, uint32_t nblk, uint32_t shift,
-    int32_t* __restrict__ share, uint32_t lo, uint32_t hi) {
+    int32_t* __restrict__ share, uint32_t lo, uint32_t hi, int32_t value_offset) {
     __shared__ uint32_t wave_counts[kWaves][kRadix];  // running counts, later wave-exclusive offsets
     __shared__ uint32_t digit_base[kRadix];
     __shared__ uint32_t scan_tmp[kThreads];
@@ -187,19 +195,37 @@ __global__ void __launch_bounds__(kThreads) scatter_kernel(
             const uint32_t dn = static_cast<uint32_t>(key[r] >> (shift + 8)) & 0xFFu;
             atomicAdd(&hist_next[static_cast<size_t>(dn) * nblk + pos / kSortTile], 1u);
         } else {
-            if (pos >= lo && pos < hi) share[pos - lo] = val[r];
+            if (pos >= lo && pos < hi) share[pos - lo] = val[r] + value_offset;
         }
     }
 }
 
+// share[i] = first + i (sequential order).
+__global__ void __launch_bounds__(kThreads) iota_kernel(int32_t* __restrict__ share, uint32_t len, int32_t first) {
+    const uint32_t i = blockIdx.x * kThreads + threadIdx.x;
+    if (i < len) share[i] = first + static_cast<int32_t>(i);
+}
+
+// Batch-level shuffle: element i of the share belongs to visit slot i / B; full batches are visited
+// in `order`, the short remainder (slots >= n_full) stays in place.
+__global__ void __launch_bounds__(kThreads) expand_batches_kernel(const int32_t* __restrict__ order,
+                                                                  uint32_t n_full, uint32_t B, int32_t base,
+                                                                  int32_t* __restrict__ share, uint32_t len) {
+    const uint32_t i = blockIdx.x * kThreads + threadIdx.x;
+    if (i >= len) return;
+    const uint32_t slot = i / B, j = i - slot * B;
+    const uint32_t batch = (slot < n_full) ? static_cast<uint32_t>(order[slot]) : slot;
+    share[i] = base + static_cast<int32_t>(batch * B + j);
+}
+
 }  // namespace
 
-hipError_t launch_epoch_sort(pgti_ctx* c, uint64_t seed, uint64_t epoch, uint32_t lo, uint32_t hi,
-                             hipStream_t s) {
-    const uint32_t n = static_cast<uint32_t>(c->n_windows);
-    const uint32_t nblk = c->sort_blocks;
-    hipLaunchKernelGGL(keygen_kernel, dim3(nblk), dim3(kThreads), 0, s, seed, epoch, n, nblk,
-                       c->d_keys[0], c->d_hist[0]);
+hipError_t launch_sorted_order(pgti_ctx* c, uint64_t seed, uint64_t epoch, const SortPlan& plan, hipStream_t s) {
+    const uint32_t n = plan.n_keys;
+    if (n == 0) return hipSuccess;
+    const uint32_t nblk = (n + kSortTile - 1) / kSortTile;
+    hipLaunchKernelGGL(keygen_kernel, dim3(nblk), dim3(kThreads), 0, s, seed, epoch, n, nblk, plan.counter_base,
+                       plan.counter_stride, c->d_keys[0], c->d_hist[0]);
     for (uint32_t pass = 0; pass < 8; ++pass) {
         uint32_t* hist = c->d_hist[pass & 1];
         uint32_t* hist_next = c->d_hist[(pass + 1) & 1];
@@ -209,15 +235,32 @@ hipError_t launch_epoch_sort(pgti_ctx* c, uint64_t seed, uint64_t epoch, uint32_
         int32_t* vout = c->d_vals[(pass + 1) & 1];
         hipLaunchKernelGGL(scan_kernel, dim3(kRadix), dim3(kThreads), 0, s, hist, c->d_tot, hist_next, nblk);
         if (pass == 0)
-            hipLaunchKernelGGL((scatter_kernel<true, false>), dim3(nblk), dim3(kThreads), 0, s, kin, vin,
-                               kout, vout, hist, c->d_tot, hist_next, n, nblk, 8 * pass, c->d_share, lo, hi);
+            hipLaunchKernelGGL((scatter_kernel<true, false>), dim3(nblk), dim3(kThreads), 0, s, kin, vin, kout, vout,
+                               hist, c->d_tot, hist_next, n, nblk, 8 * pass, plan.out, plan.out_lo, plan.out_hi,
+                               plan.value_offset);
         else if (pass < 7)
-            hipLaunchKernelGGL((scatter_kernel<false, false>), dim3(nblk), dim3(kThreads), 0, s, kin, vin,
-                               kout, vout, hist, c->d_tot, hist_next, n, nblk, 8 * pass, c->d_share, lo, hi);
+            hipLaunchKernelGGL((scatter_kernel<false, false>), dim3(nblk), dim3(kThreads), 0, s, kin, vin, kout, vout,
+                               hist, c->d_tot, hist_next, n, nblk, 8 * pass, plan.out, plan.out_lo, plan.out_hi,
+                               plan.value_offset);
         else
-            hipLaunchKernelGGL((scatter_kernel<false, true>), dim3(nblk), dim3(kThreads), 0, s, kin, vin,
-                               kout, vout, hist, c->d_tot, hist_next, n, nblk, 8 * pass, c->d_share, lo, hi);
+            hipLaunchKernelGGL((scatter_kernel<false, true>), dim3(nblk), dim3(kThreads), 0, s, kin, vin, kout, vout,
+                               hist, c->d_tot, hist_next, n, nblk, 8 * pass, plan.out, plan.out_lo, plan.out_hi,
+                               plan.value_offset);
     }
+    return hipGetLastError();
+}
+
+hipError_t launch_sequential_order(int32_t* share, uint32_t len, int32_t first, hipStream_t s) {
+    if (len == 0) return hipSuccess;
+    hipLaunchKernelGGL(iota_kernel, dim3((len + kThreads - 1) / kThreads), dim3(kThreads), 0, s, share, len, first);
+    return hipGetLastError();
+}
+
+hipError_t launch_expand_batches(const int32_t* order, uint32_t n_full, uint32_t B, int32_t base, int32_t* share,
+                                 uint32_t len, hipStream_t s) {
+    if (len == 0) return hipSuccess;
+    hipLaunchKernelGGL(expand_batches_kernel, dim3((len + kThreads - 1) / kThreads), dim3(kThreads), 0, s, order,
+                       n_full, B, base, share, len);
     return hipGetLastError();
 }
 

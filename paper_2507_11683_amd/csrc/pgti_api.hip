@@ -366,19 +366,30 @@ int pgti_get_stats(pgti_ctx* c, float* mean_out, float* std_out) {
     return PGTI_OK;
 }
 
-int pgti_epoch_indices(pgti_ctx* c, uint64_t seed, uint64_t epoch, uint32_t rank, uint32_t world,
-                       int64_t* n_share) {
+int pgti_epoch_indices_ex(pgti_ctx* c, const pgti_epoch_spec* spec, int64_t* n_share) {
     g_error[0] = 0;
     if (!c) return fail(PGTI_ERR_ARG, "null context");
+    if (!spec) return fail(PGTI_ERR_ARG, "null epoch spec");
     if (!c->loaded) return fail(PGTI_ERR_STATE, "no series loaded");
-    if (world == 0) return fail(PGTI_ERR_RANGE, "world must be at least 1");
-    if (rank >= world) return fail(PGTI_ERR_RANGE, "rank %u not in [0, %u)", rank, world);
+    if (spec->order != PGTI_ORDER_SHUFFLE && spec->order != PGTI_ORDER_SEQUENTIAL &&
+        spec->order != PGTI_ORDER_BATCH_SHUFFLE)
+        return fail(PGTI_ERR_ARG, "unknown epoch order %d", spec->order);
+    if (spec->world == 0) return fail(PGTI_ERR_RANGE, "world must be at least 1");
+    if (spec->rank >= spec->world) return fail(PGTI_ERR_RANGE, "rank %u not in [0, %u)", spec->rank, spec->world);
+    const int64_t first_start = spec->first_start;
+    if (first_start < 0 || first_start > c->n_windows)
+        return fail(PGTI_ERR_RANGE, "first_start %lld not in [0, %lld]", (long long)first_start, (long long)c->n_windows);
+    const int64_t n_starts = spec->n_starts < 0 ? c->n_windows - first_start : spec->n_starts;
+    if (n_starts > c->n_windows - first_start)
+        return fail(PGTI_ERR_RANGE, "starts [%lld, %lld) exceed the %lld windows", (long long)first_start,
+                    (long long)(first_start + n_starts), (long long)c->n_windows);
     DeviceGuard guard(c->device);
     if (guard.status != hipSuccess) return fail_hip(guard.status, "hipSetDevice");
 
-    const uint64_t n = static_cast<uint64_t>(c->n_windows);
-    const uint64_t lo = (static_cast<uint64_t>(rank) * n) / world;  // < 2^32 * 2^31: no overflow
-    const uint64_t hi = ((static_cast<uint64_t>(rank) + 1) * n) / world;
+    const uint64_t n = static_cast<uint64_t>(n_starts);
+    const uint64_t lo = (static_cast<uint64_t>(spec->rank) * n) / spec->world;  // < 2^32 * 2^31: no overflow
+    const uint64_t hi = ((static_cast<uint64_t>(spec->rank) + 1) * n) / spec->world;
+    const uint32_t len = static_cast<uint32_t>(hi - lo);
 
     // The share buffer is about to be overwritten: order the sort behind every batch build that
     // was enqueued through this context since the last sort.
@@ -388,14 +399,43 @@ int pgti_epoch_indices(pgti_ctx* c, uint64_t seed, uint64_t epoch, uint32_t rank
     }
     c->n_tracked = 0;
 
-    PGTI_HIP_TRY(launch_epoch_sort(c, seed, epoch, static_cast<uint32_t>(lo), static_cast<uint32_t>(hi),
-                                   c->work_stream));
-    PGTI_HIP_TRY(hipEventRecord(c->ev_share_ready, c->work_stream));
+    hipStream_t ws = c->work_stream;
+    if (spec->order == PGTI_ORDER_SHUFFLE) {
+        SortPlan plan{static_cast<uint32_t>(n), 0, 1, c->d_share, static_cast<uint32_t>(lo),
+                      static_cast<uint32_t>(hi), static_cast<int32_t>(first_start)};
+        PGTI_HIP_TRY(launch_sorted_order(c, spec->seed, spec->epoch, plan, ws));
+    } else if (spec->order == PGTI_ORDER_SEQUENTIAL) {
+        PGTI_HIP_TRY(launch_sequential_order(c->d_share, len, static_cast<int32_t>(first_start + lo), ws));
+    } else {
+        // Order of the full batches of the partition [lo, hi): keys on the position of each batch's
+        // first element; the sorted batch numbers pass through d_vals[0], then expand to starts.
+        const uint32_t n_full = len / static_cast<uint32_t>(c->B);
+        SortPlan plan{n_full, lo, static_cast<uint64_t>(c->B), c->d_vals[0], 0, n_full, 0};
+        PGTI_HIP_TRY(launch_sorted_order(c, spec->seed, spec->epoch, plan, ws));
+        PGTI_HIP_TRY(launch_expand_batches(c->d_vals[0], n_full, static_cast<uint32_t>(c->B),
+                                           static_cast<int32_t>(first_start + lo), c->d_share, len, ws));
+    }
+    PGTI_HIP_TRY(hipEventRecord(c->ev_share_ready, ws));
     c->share_lo = static_cast<int64_t>(lo);
     c->share_hi = static_cast<int64_t>(hi);
     c->have_share = true;
+    c->share_consecutive = (spec->order != PGTI_ORDER_SHUFFLE);
     if (n_share) *n_share = static_cast<int64_t>(hi - lo);
     return PGTI_OK;
+}
+
+int pgti_epoch_indices(pgti_ctx* c, uint64_t seed, uint64_t epoch, uint32_t rank, uint32_t world,
+                       int64_t* n_share) {
+    pgti_epoch_spec spec;
+    memset(&spec, 0, sizeof(spec));
+    spec.order = PGTI_ORDER_SHUFFLE;
+    spec.first_start = 0;
+    spec.n_starts = -1;
+    spec.seed = seed;
+    spec.epoch = epoch;
+    spec.rank = rank;
+    spec.world = world;
+    return pgti_epoch_indices_ex(c, &spec, n_share);
 }
 
 int64_t pgti_get_indices(pgti_ctx* c, int32_t* host_out, int64_t capacity) {
@@ -461,8 +501,9 @@ static int64_t build_range(pgti_ctx* c, int64_t first_batch, int64_t k, float* o
     // Samples are consecutive in the share and in the outputs, so several batches are one launch
     // with more samples; the grid's sample dimension holds at most 65,535.
     const int64_t x_stride = static_cast<int64_t>(c->P) * c->R, y_stride = static_cast<int64_t>(c->Q) * c->R;
-    for (int64_t done = 0; done < count; done += 65535) {
-        const int32_t part = static_cast<int32_t>((count - done < 65535) ? (count - done) : 65535);
+    const int64_t max_part = (65535 / c->B) * static_cast<int64_t>(c->B);  // whole batches per launch
+    for (int64_t done = 0; done < count; done += max_part) {
+        const int32_t part = static_cast<int32_t>((count - done < max_part) ? (count - done) : max_part);
         PGTI_HIP_TRY(launch_batch_gather(c, c->d_share + first + done, part, out_x + done * x_stride,
                                          out_y + done * y_stride, s));
     }

@@ -59,6 +59,7 @@ struct pgti_ctx {
     int32_t* d_share = nullptr;                // this rank's starts, capacity n_windows
     uint32_t sort_blocks = 0;
     bool have_share = false;
+    bool share_consecutive = false;  // batches hold consecutive starts (sequential / batch-shuffled order)
     int64_t share_lo = 0, share_hi = 0;
     hipEvent_t ev_share_ready = nullptr;
 
@@ -93,9 +94,20 @@ hipError_t launch_reduce_rows(const double* row_acc, int64_t T, int32_t N, int32
 
 // ---- epoch_sort.hip -------------------------------------------------------------------------
 constexpr uint32_t kSortTile = 2048;  // keys per workgroup per pass
-// Keys, 8 stable counting passes, and the rank's slice [lo, hi) of the sorted starts -> share.
-hipError_t launch_epoch_sort(pgti_ctx* c, uint64_t seed, uint64_t epoch, uint32_t lo, uint32_t hi,
-                             hipStream_t s);
+// One sorted order: n_keys keys key(seed, epoch, counter_base + i*counter_stride), 8 stable counting
+// passes; positions [out_lo, out_hi) of the sorted index list, plus value_offset, land in out[].
+// out may be c->d_vals[0] (free during the last pass) when the order is an intermediate result.
+struct SortPlan {
+    uint32_t n_keys;
+    uint64_t counter_base, counter_stride;
+    int32_t* out;
+    uint32_t out_lo, out_hi;
+    int32_t value_offset;
+};
+hipError_t launch_sorted_order(pgti_ctx* c, uint64_t seed, uint64_t epoch, const SortPlan& plan, hipStream_t s);
+hipError_t launch_sequential_order(int32_t* share, uint32_t len, int32_t first, hipStream_t s);
+hipError_t launch_expand_batches(const int32_t* order, uint32_t n_full, uint32_t B, int32_t base, int32_t* share,
+                                 uint32_t len, hipStream_t s);
 
 // ---- batch_gather.hip -----------------------------------------------------------------------
 // Enqueues the fused gather + standardise of `count` samples whose starts are d_starts[0..count).

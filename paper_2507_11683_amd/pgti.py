@@ -39,6 +39,17 @@ SIGNATURES = {
     "pgti_last_error": (ctypes.c_char_p, []),
 }
 
+PGTI_ORDER_SHUFFLE, PGTI_ORDER_SEQUENTIAL, PGTI_ORDER_BATCH_SHUFFLE = 0, 1, 2
+
+
+class EpochSpec(ctypes.Structure):
+    """Mirror of pgti_epoch_spec."""
+    _fields_ = [("order", _i32), ("reserved", _i32), ("first_start", _i64), ("n_starts", _i64),
+                ("seed", _u64), ("epoch", _u64), ("rank", _u32), ("world", _u32)]
+
+
+SIGNATURES["pgti_epoch_indices_ex"] = (ctypes.c_int, [_vp, ctypes.POINTER(EpochSpec), ctypes.POINTER(_i64)])
+
 _lib = None
 
 
@@ -150,6 +161,14 @@ class Context:
     def epoch_indices(self, seed: int, epoch: int, rank: int = 0, world: int = 1) -> int:
         n = _i64(0)
         _check(self._lib.pgti_epoch_indices(self._h, seed, epoch, rank, world, ctypes.byref(n)))
+        return int(n.value)
+
+    # -- pgti_epoch_indices_ex --------------------------------------------------------------------
+    def epoch_indices_ex(self, order: int, seed: int = 0, epoch: int = 0, rank: int = 0, world: int = 1,
+                         first_start: int = 0, n_starts: int = -1) -> int:
+        spec = EpochSpec(order, 0, first_start, n_starts, seed, epoch, rank, world)
+        n = _i64(0)
+        _check(self._lib.pgti_epoch_indices_ex(self._h, ctypes.byref(spec), ctypes.byref(n)))
         return int(n.value)
 
     # -- pgti_get_indices -------------------------------------------------------------------------

@@ -265,6 +265,137 @@ def test_epoch_order_sizes(n):
         assert np.array_equal(np.concatenate(pieces), oracle.epoch_perm(3, 1, n))
 
 
+ORDERS = {"shuffle": 0, "sequential": 1, "batch_shuffle": 2}
+
+
+@pytest.mark.parametrize("order_name", list(ORDERS))
+@pytest.mark.parametrize("n,B,first,count,world", [
+    (1977, 64, 0, -1, 1), (1977, 64, 0, 1384, 1), (1977, 64, 1384, 198, 2), (1977, 64, 1582, -1, 3),
+    (34249, 64, 0, 23974, 4), (10000, 7, 123, 5000, 16), (105097, 32, 0, -1, 16), (50, 64, 0, -1, 1),
+    (4100, 2, 0, -1, 1), (300, 64, 10, 0, 1)])
+def test_epoch_orders_and_ranges(order_name, n, B, first, count, world):
+    # global shuffle / sequential / batch-level shuffle over train, validation and test ranges
+    order = ORDERS[order_name]
+    P = Q = 1
+    series = np.zeros((n + P + Q - 1, 1, 1), np.float32)
+    n_starts = n - first if count < 0 else count
+    with pgti.Context(0) as ctx:
+        ctx.load_series(series, P, Q, B, pgti.PGTI_F32, [0.0], [1.0])
+        for epoch in (0, 5):
+            for rank in sorted({0, world // 2, world - 1}):
+                got_n = ctx.epoch_indices_ex(order, seed=21, epoch=epoch, rank=rank, world=world,
+                                             first_start=first, n_starts=count)
+                want = oracle.epoch_indices_ex(order, n, first, n_starts, B, 21, epoch, rank, world)
+                assert got_n == len(want)
+                if got_n:
+                    assert np.array_equal(ctx.get_indices(), want), (order_name, epoch, rank)
+                    assert ctx.num_batches() == -(-got_n // B)
+        for bad in [dict(first_start=-1), dict(first_start=n + 1), dict(first_start=first, n_starts=n - first + 1),
+                    dict(rank=world), dict(order=3)]:
+            args = dict(order=order, seed=1, epoch=0, rank=0, world=world, first_start=0, n_starts=-1)
+            args.update(bad)
+            with pytest.raises(pgti.PgtiError) as e:
+                ctx.epoch_indices_ex(**args)
+            assert e.value.status == (pgti.PGTI_ERR_ARG if "order" in bad else pgti.PGTI_ERR_RANGE)
+
+
+@pytest.mark.parametrize("order_name", ["sequential", "batch_shuffle"])
+@pytest.mark.parametrize("storage_name", ["f32", "bf16"])
+def test_batches_of_consecutive_starts(order_name, storage_name):
+    # consecutive starts share all but one row: every batch of a validation-range pass, bit for bit
+    w = workloads.WORKLOADS["tiny"]
+    series = workloads.make_series(w)
+    mean, std = oracle.series_stats(series)
+    storage = pgti.PGTI_F32 if storage_name == "f32" else pgti.PGTI_BF16
+    n = w.n_windows
+    first, count = round(n * 0.7), round(n * 0.1)
+    with pgti.Context(0) as ctx:
+        ctx.load_series(series, w.P, w.Q, w.B, storage, mean, std)
+        ctx.epoch_indices_ex(ORDERS[order_name], seed=4, epoch=1, first_start=first, n_starts=count)
+        share = ctx.get_indices()
+        assert np.array_equal(share, oracle.epoch_indices_ex(ORDERS[order_name], n, first, count, w.B, 4, 1))
+        _check_batches(ctx, _oracle_series(series, storage), storage, w.P, w.Q, w.B, mean, std, share,
+                       range(ctx.num_batches()))
+
+
+ROW_GEOMETRIES = [
+    # T,   N,    F, P,  Q,  B     rows start on a 16-byte boundary (R % 4 == 0): the row-centric kernel
+    (200, 1116, 2, 12, 12, 8),
+    (300, 6, 2, 12, 12, 32),
+    (150, 33, 4, 6, 2, 7),
+    (400, 320, 1, 8, 8, 64),
+    (90, 4002, 2, 4, 8, 5),
+    (120, 4, 3, 2, 5, 9),     # F = 3 with R = 12
+    (100, 8, 12, 3, 3, 4),    # F = 12 > 8
+    (60, 2, 2, 12, 12, 64),   # B larger than the whole range
+    (40, 4, 1, 1, 1, 3),
+]
+
+
+@pytest.mark.parametrize("order_name", ["sequential", "batch_shuffle"])
+@pytest.mark.parametrize("storage_name", ["f32", "bf16"])
+@pytest.mark.parametrize("geom", ROW_GEOMETRIES, ids=lambda g: "T%d_N%d_F%d_P%d_Q%d_B%d" % g)
+def test_row_centric_kernel(geom, storage_name, order_name):
+    T, N, F, P, Q, B = geom
+    rng = np.random.default_rng(sum((i + 3) * v for i, v in enumerate(geom)))
+    series = _special_series(rng, T, N, F)
+    mean = rng.normal(40, 10, F).astype(np.float32)
+    std = rng.uniform(0.3, 25, F).astype(np.float32)
+    storage = pgti.PGTI_F32 if storage_name == "f32" else pgti.PGTI_BF16
+    ser_o = _oracle_series(series, storage)
+    n = T - P - Q + 1
+    canary = 4321.0
+    with pgti.Context(0) as ctx:
+        ctx.load_series(series, P, Q, B, storage, mean, std)
+        for first, count, rank, world in [(0, n, 0, 1), (n // 3, n // 2, 1, 2), (n - 1, 1, 0, 1)]:
+            got_n = ctx.epoch_indices_ex(ORDERS[order_name], seed=8, epoch=2, rank=rank, world=world,
+                                         first_start=first, n_starts=count)
+            share = ctx.get_indices()
+            assert np.array_equal(share, oracle.epoch_indices_ex(ORDERS[order_name], n, first, count, B, 8, 2, rank, world))
+            nb = ctx.num_batches()
+            # one batch per launch, every batch
+            _check_batches(ctx, ser_o, storage, P, Q, B, mean, std, share, range(nb))
+            # several batches per launch, including the short last one
+            for fb, k in {(0, nb), (nb // 2, nb - nb // 2), (max(0, nb - 3), min(3, nb))}:
+                x = torch.full((k, B, P, N, F), canary, dtype=torch.float32, device="cuda")
+                y = torch.full((k, B, Q, N, F), canary, dtype=torch.float32, device="cuda")
+                total = ctx.build_batches(fb, k, x, y)
+                torch.cuda.synchronize()
+                starts = share[fb * B:(fb + k) * B]
+                assert total == len(starts)
+                wx, wy = oracle.build_batch(ser_o, storage, P, Q, mean, std, starts)
+                gx = x.cpu().numpy().reshape(k * B, P, N, F)
+                gy = y.cpu().numpy().reshape(k * B, Q, N, F)
+                assert _bits_equal(gx[:total], wx) and _bits_equal(gy[:total], wy), (fb, k)
+                assert np.all(gx[total:] == canary) and np.all(gy[total:] == canary)
+
+
+def test_row_centric_statewide_sampled(statewide_series):
+    # full size, the launch shape bench.py --order sequential times (4 batches of 32 per launch)
+    w = workloads.WORKLOADS["statewide"]
+    mean, std = _sampled_stats(statewide_series)
+    k = 4
+    with pgti.Context(0) as ctx:
+        ctx.load_series(statewide_series, w.P, w.Q, w.B, pgti.PGTI_F32, mean, std)
+        for order_name in ("sequential", "batch_shuffle"):
+            ctx.epoch_indices_ex(ORDERS[order_name], seed=w.seed, epoch=0)
+            share = ctx.get_indices()
+            assert np.array_equal(share, oracle.epoch_indices_ex(ORDERS[order_name], w.n_windows, 0, w.n_windows,
+                                                                 w.B, w.seed, 0))
+            nb = ctx.num_batches()
+            x = torch.empty((k, w.B, w.P, w.N, w.F), dtype=torch.float32, device="cuda")
+            y = torch.empty((k, w.B, w.Q, w.N, w.F), dtype=torch.float32, device="cuda")
+            for first in (0, 1000, nb - k):
+                total = ctx.build_batches(first, k, x, y)
+                torch.cuda.synchronize()
+                starts = share[first * w.B:(first + k) * w.B]
+                assert total == len(starts)
+                wx, wy = oracle.build_batch(statewide_series, oracle.F32, w.P, w.Q, mean, std, starts)
+                gx = x.cpu().numpy().reshape(k * w.B, w.P, w.N, w.F)[:total]
+                gy = y.cpu().numpy().reshape(k * w.B, w.Q, w.N, w.F)[:total]
+                assert _bits_equal(gx, wx) and _bits_equal(gy, wy), (order_name, first)
+
+
 def test_epoch_indices_reproducible_and_reentrant():
     w = workloads.WORKLOADS["tiny"]
     series = workloads.make_series(w)
