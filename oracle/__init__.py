@@ -80,6 +80,12 @@ def _load():
         lib.oracle_alg1_train_stats.argtypes = [vp, i64, i64, i64, i64, i64,
                                                 ctypes.POINTER(ctypes.c_double),
                                                 ctypes.POINTER(ctypes.c_double)]
+        lib.oracle_alg1_train_stats_fraction.restype = ctypes.c_int
+        lib.oracle_alg1_train_stats_fraction.argtypes = [vp, i64, i64, i64, i64, i64, ctypes.c_double,
+                                                         ctypes.POINTER(ctypes.c_double),
+                                                         ctypes.POINTER(ctypes.c_double)]
+        lib.oracle_add_time_of_day.restype = ctypes.c_int
+        lib.oracle_add_time_of_day.argtypes = [vp, i64, i64, i64, i64, vp]
         lib.oracle_series_stats.restype = ctypes.c_int
         lib.oracle_series_stats.argtypes = [vp, i64, i64, i64, vp, vp]
         _lib = lib
@@ -231,6 +237,24 @@ def alg1_train_stats(data: np.ndarray, P: int, Q: int) -> tuple[float, float]:
     _check(_load().oracle_alg1_train_stats(_ptr(data), T, N, F, P, Q, ctypes.byref(m),
                                            ctypes.byref(s)), "alg1_train_stats")
     return float(m.value), float(s.value)
+
+
+def alg1_train_stats_fraction(data: np.ndarray, P: int, Q: int, fraction: float) -> tuple[float, float]:
+    data = _c(data, np.float32)
+    T, N, F = data.shape
+    m, s = ctypes.c_double(), ctypes.c_double()
+    _check(_load().oracle_alg1_train_stats_fraction(_ptr(data), T, N, F, P, Q, fraction, ctypes.byref(m),
+                                                    ctypes.byref(s)), "alg1_train_stats_fraction")
+    return float(m.value), float(s.value)
+
+
+def add_time_of_day(data: np.ndarray, period: int) -> np.ndarray:
+    """[T,N,F] -> [T,N,F+1] with the time-of-day channel (t mod period)/period appended."""
+    data = _c(data, np.float32)
+    T, N, F = data.shape
+    out = np.empty((T, N, F + 1), dtype=np.float32)
+    _check(_load().oracle_add_time_of_day(_ptr(data), T, N, F, period, _ptr(out)), "add_time_of_day")
+    return out
 
 
 def series_stats(data: np.ndarray) -> tuple[np.ndarray, np.ndarray]:

@@ -315,12 +315,14 @@ int oracle_alg1_preprocess(const float* data, int64_t T, int64_t N, int64_t F, i
  * (population, divisor = count) over every element of x_train, the first
  * round(0.70 * n) windows of the stacked x.  Elements near the ends of the training range
  * appear in fewer windows and so weigh less; features are mixed.  fp64 accumulation,
- * window-major order.  round() is round-half-to-even as in the listing's language. */
-int oracle_alg1_train_stats(const float* data, int64_t T, int64_t N, int64_t F, int64_t P,
-                            int64_t Q, double* mean_out, double* std_out) {
+ * window-major order.  round() is round-half-to-even as in the listing's language.  The
+ * listing fixes the training fraction at 0.70 and its caption allows other splits, hence the
+ * parameter. */
+int oracle_alg1_train_stats_fraction(const float* data, int64_t T, int64_t N, int64_t F, int64_t P,
+                                     int64_t Q, double fraction, double* mean_out, double* std_out) {
     if (!data || !mean_out || !std_out) return ORACLE_ERR_ARG;
     int64_t n = oracle_window_count(T, P, Q);
-    int64_t n_train = (int64_t)nearbyint((double)n * 0.70);
+    int64_t n_train = (int64_t)nearbyint((double)n * fraction);
     int64_t row = N * F;
     int64_t count = n_train * P * row;
     if (count <= 0) return ORACLE_ERR_ARG;
@@ -336,6 +338,31 @@ int oracle_alg1_train_stats(const float* data, int64_t T, int64_t N, int64_t F, 
         }
     *mean_out = mean;
     *std_out = sqrt(sq / (double)count);
+    return ORACLE_OK;
+}
+
+/* Algorithm 1 as listed: the training part is the first 70 % of the windows. */
+int oracle_alg1_train_stats(const float* data, int64_t T, int64_t N, int64_t F, int64_t P,
+                            int64_t Q, double* mean_out, double* std_out) {
+    return oracle_alg1_train_stats_fraction(data, T, N, F, P, Q, 0.70, mean_out, std_out);
+}
+
+/* Stage 1 of the preprocessing (the data-growth figure of Sec. 3.3: time-of-day information
+ * is added to the data as one more feature, the same value for every node of a timestep).
+ * out[t, node, 0..F-1] = data[t, node, :], out[t, node, F] = (t mod period) / period, the
+ * quotient taken in binary32 (both operands are small integers, exactly representable). */
+int oracle_add_time_of_day(const float* data, int64_t T, int64_t N, int64_t F, int64_t period,
+                           float* out) {
+    if (!data || !out || T <= 0 || N <= 0 || F <= 0 || period <= 0 || period >= (1 << 24))
+        return ORACLE_ERR_ARG;
+    for (int64_t t = 0; t < T; ++t) {
+        volatile float tod = (float)(t % period) / (float)period;
+        for (int64_t node = 0; node < N; ++node) {
+            for (int64_t f = 0; f < F; ++f)
+                out[(t * N + node) * (F + 1) + f] = data[(t * N + node) * F + f];
+            out[(t * N + node) * (F + 1) + F] = tod;
+        }
+    }
     return ORACLE_OK;
 }
 

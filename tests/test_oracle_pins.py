@@ -518,3 +518,44 @@ def test_consecutive_starts_share_rows():
     for s in starts:
         rows.update(range(s, s + P + Q))
     assert len(rows) == B + P + Q - 1
+
+
+# ----------------------------------------------------------------------------------------------
+# preprocessing stage 1 (time of day) and Algorithm 1's training statistics with another split
+# ----------------------------------------------------------------------------------------------
+def test_time_of_day_channel_is_tiled_over_nodes():
+    rng = np.random.default_rng(31)
+    T, N, F, period = 700, 5, 1, 288
+    data = rng.normal(60, 9, (T, N, F)).astype(np.float32)
+    out = oracle.add_time_of_day(data, period)
+    assert out.shape == (T, N, F + 1)
+    assert np.array_equal(out[..., :F], data)
+    # the usual construction: one value per timestep, tiled over the nodes
+    time_ind = ((np.arange(T) % period).astype(np.float32) / np.float32(period)).astype(np.float32)
+    tiled = np.tile(time_ind[:, None, None], (1, N, 1))
+    assert np.array_equal(out[..., F:].view(np.uint32), tiled.view(np.uint32))
+    assert out[0, 0, F] == 0.0 and out[period, 3, F] == 0.0 and out[period - 1, 0, F] == np.float32(287) / np.float32(288)
+    # it is the channel the benchmark inputs carry
+    from paper_2507_11683_amd import workloads
+    w = workloads.WORKLOADS["tiny"]
+    series = workloads.make_series(w)
+    assert np.array_equal(oracle.add_time_of_day(np.ascontiguousarray(series[..., :1]), 288), series)
+
+
+def test_alg1_train_stats_other_fraction_and_weights():
+    rng = np.random.default_rng(37)
+    T, N, F, P, Q = 80, 3, 2, 5, 3
+    data = rng.normal(50, 10, (T, N, F)).astype(np.float32)
+    n = T - P - Q + 1
+    for frac in (0.7, 0.5, 1.0):
+        n_train = round(n * frac)
+        x_train = np.stack([data[w:w + P] for w in range(n_train)], axis=0).astype(np.float64)
+        mean, std = oracle.alg1_train_stats_fraction(data, P, Q, frac)
+        assert abs(mean - x_train.mean()) < 1e-9 and abs(std - x_train.std()) < 1e-9
+        # equivalent row-weighted form: row t appears in min(t, n_train-1) - max(0, t-P+1) + 1 training windows
+        t = np.arange(n_train + P - 1)
+        wgt = np.minimum(t, n_train - 1) - np.maximum(0, t - P + 1) + 1
+        rows = data[:n_train + P - 1].astype(np.float64)
+        wmean = (wgt[:, None, None] * rows).sum() / (wgt.sum() * N * F)
+        assert abs(mean - wmean) < 1e-9 and wgt.sum() == n_train * P
+    assert oracle.alg1_train_stats(data, P, Q) == oracle.alg1_train_stats_fraction(data, P, Q, 0.70)
