@@ -78,6 +78,49 @@ int pgti_load_series_device(pgti_ctx* c, const float* device_series, int64_t T, 
                             int32_t F, int32_t P, int32_t Q, int32_t B, pgti_dtype storage,
                             const float* mean, const float* std);
 
+/*
+ * Load with on-device preprocessing (Sec. 4.1: GPU-index-batching performs the preprocessing on the
+ * GPU as well; Algorithm 1 and the data-growth figure of Sec. 3.3 name its steps).
+ *
+ * series: fp32 [T, N, F_in], HOST or (source_on_device != 0) DEVICE.
+ * time_of_day_period > 0: stage 1 of the preprocessing, one more feature is appended to every
+ *     node, (t mod period) / period (quotient in binary32), so the resident series has
+ *     F = F_in + 1 features; 0: F = F_in.
+ * stats_rule
+ *     PGTI_STATS_GIVEN           mean / std (HOST, F entries each) as passed
+ *     PGTI_STATS_FEATURE_GLOBAL  per feature: mean and population standard deviation of all T*N values
+ *     PGTI_STATS_ALG1_TRAIN      Algorithm 1: ONE scalar mean and population standard deviation over
+ *                                every element of x_train, the first round(train_fraction * n) windows
+ *                                of the stacked x (round half to even; the listing uses 0.70); rows
+ *                                near the ends of the training range count in fewer windows, features
+ *                                are mixed; the scalar is used for every feature.
+ *     Computed statistics are accumulated in fp64 on the device and rounded to fp32 once; they see
+ *     the fp32 values (before any bf16 rounding), including the time-of-day feature.
+ * Other fields as the arguments of pgti_load_series.  Errors: as pgti_load_series.
+ */
+typedef enum {
+    PGTI_STATS_GIVEN = 0,
+    PGTI_STATS_FEATURE_GLOBAL = 1,
+    PGTI_STATS_ALG1_TRAIN = 2
+} pgti_stats_rule;
+
+typedef struct pgti_load_spec {
+    int64_t T;
+    int32_t N;
+    int32_t F_in;               /* features in the source array */
+    int32_t P, Q, B;
+    int32_t storage;            /* a pgti_dtype */
+    int32_t source_on_device;   /* 0: host pointer, 1: device pointer */
+    int32_t stats_rule;         /* a pgti_stats_rule */
+    int32_t time_of_day_period; /* 0: none */
+    int32_t reserved;           /* set to 0 */
+    double train_fraction;      /* PGTI_STATS_ALG1_TRAIN only */
+    const float* mean;          /* PGTI_STATS_GIVEN only */
+    const float* std;
+} pgti_load_spec;
+
+int pgti_load_series_ex(pgti_ctx* c, const float* series, const pgti_load_spec* spec);
+
 /* Reads back the statistics in use (HOST, F floats each; either may be NULL). */
 int pgti_get_stats(pgti_ctx* c, float* mean_out, float* std_out);
 

@@ -105,15 +105,44 @@ int check_stats(const float* mean, const float* stdev, int32_t F) {
     return PGTI_OK;
 }
 
-// The load itself.  `src` is fp32 [T, N, F], on the host or (src_on_device) on the device.
-int load_impl(pgti_ctx* c, const float* src, bool src_on_device, int64_t T, int32_t N, int32_t F, int32_t P,
-              int32_t Q, int32_t B, pgti_dtype storage, const float* mean, const float* stdev) {
+// The load itself.  `src` is fp32 [T, N, F_in], on the host or on the device (spec->source_on_device).
+int load_impl(pgti_ctx* c, const float* src, const pgti_load_spec* spec) {
     if (!c) return fail(PGTI_ERR_ARG, "null context");
+    if (!spec) return fail(PGTI_ERR_ARG, "null load spec");
     if (!src) return fail(PGTI_ERR_ARG, "null series pointer");
-    if ((mean == nullptr) != (stdev == nullptr)) return fail(PGTI_ERR_ARG, "pass both mean and std, or neither");
+    const int64_t T = spec->T;
+    const int32_t N = spec->N, F_in = spec->F_in, P = spec->P, Q = spec->Q, B = spec->B;
+    const int32_t period = spec->time_of_day_period;
+    const pgti_dtype storage = static_cast<pgti_dtype>(spec->storage);
+    const bool src_on_device = spec->source_on_device != 0;
+    const float* mean = spec->mean;
+    const float* stdev = spec->std;
+    if (period < 0 || period >= (1 << 24)) return fail(PGTI_ERR_ARG, "time_of_day_period %d not in [0, 2^24)", period);
+    if (F_in <= 0) return fail(PGTI_ERR_ARG, "F_in must be positive");
+    const bool synth = period > 0;
+    const int32_t F = F_in + (synth ? 1 : 0);
     if (int rc = check_geometry(T, N, F, P, Q, B, storage)) return rc;
-    if (mean)
-        if (int rc = check_stats(mean, stdev, F)) return rc;
+    const int64_t n = T - (static_cast<int64_t>(P) + Q) + 1;
+    int64_t n_train = 0;
+    switch (spec->stats_rule) {
+        case PGTI_STATS_GIVEN:
+            if (!mean || !stdev) return fail(PGTI_ERR_ARG, "PGTI_STATS_GIVEN needs both mean and std");
+            if (int rc = check_stats(mean, stdev, F)) return rc;
+            break;
+        case PGTI_STATS_FEATURE_GLOBAL:
+            break;
+        case PGTI_STATS_ALG1_TRAIN: {
+            if (!(spec->train_fraction > 0.0) || !(spec->train_fraction <= 1.0))
+                return fail(PGTI_ERR_ARG, "train_fraction %g not in (0, 1]", spec->train_fraction);
+            n_train = static_cast<int64_t>(std::nearbyint(static_cast<double>(n) * spec->train_fraction));
+            if (n_train < 1) return fail(PGTI_ERR_RANGE, "training part of %lld windows is empty", (long long)n);
+            if (n_train > n) n_train = n;
+            break;
+        }
+        default:
+            return fail(PGTI_ERR_ARG, "unknown statistics rule %d", spec->stats_rule);
+    }
+    const bool need_stats = spec->stats_rule != PGTI_STATS_GIVEN;
 
     DeviceGuard guard(c->device);
     if (guard.status != hipSuccess) return fail_hip(guard.status, "hipSetDevice");
@@ -122,11 +151,9 @@ int load_impl(pgti_ctx* c, const float* src, bool src_on_device, int64_t T, int3
     free_series(c);
     c->n_tracked = 0;
 
-    const int64_t R = static_cast<int64_t>(N) * F;
+    const int64_t R = static_cast<int64_t>(N) * F, R_in = static_cast<int64_t>(N) * F_in;
     const size_t elems = static_cast<size_t>(T) * R;
     const size_t store_bytes = (storage == PGTI_F32) ? 4 : 2;
-    const int64_t n = T - (static_cast<int64_t>(P) + Q) + 1;
-    const bool need_stats = (mean == nullptr);
 
     auto alloc = [&](auto** p, size_t bytes) -> int {
         hipError_t e = hipMalloc(reinterpret_cast<void**>(p), bytes < 256 ? 256 : bytes);
@@ -161,25 +188,25 @@ int load_impl(pgti_ctx* c, const float* src, bool src_on_device, int64_t T, int3
     int64_t chunk_rows = (64ll << 20) / (R * 4);
     chunk_rows = (chunk_rows / 4) * 4;
     if (chunk_rows < 4) chunk_rows = 4;
-    const size_t chunk_bytes = static_cast<size_t>(chunk_rows) * R * 4;
+    const size_t chunk_bytes_in = static_cast<size_t>(chunk_rows) * R_in * 4;
 
     LoadScratch tmp;
     const bool src_pinned = !src_on_device && host_pointer_is_pinned(src);
     const bool via_pinned_staging = !src_on_device && !src_pinned;
-    // A device-side fp32 view of each chunk is needed unless fp32 storage receives it directly.
-    const bool via_device_staging = !src_on_device && storage == PGTI_BF16;
+    // A host chunk lands in a device staging buffer unless it can go straight into the fp32 store.
+    const bool via_device_staging = !src_on_device && (storage == PGTI_BF16 || synth);
     for (int k = 0; k < 2; ++k) {
         PGTI_HIP_TRY(hipEventCreateWithFlags(&tmp.done[k], hipEventDisableTiming));
         if (via_pinned_staging) {
-            hipError_t e = hipHostMalloc(&tmp.pinned[k], chunk_bytes, hipHostMallocDefault);
+            hipError_t e = hipHostMalloc(&tmp.pinned[k], chunk_bytes_in, hipHostMallocDefault);
             if (e != hipSuccess) {
                 (void)hipGetLastError();
                 free_series(c);
-                return fail(PGTI_ERR_OOM, "pinned staging allocation of %zu bytes failed", chunk_bytes);
+                return fail(PGTI_ERR_OOM, "pinned staging allocation of %zu bytes failed", chunk_bytes_in);
             }
         }
         if (via_device_staging)
-            if (int rc = alloc(&tmp.stage[k], chunk_bytes)) return rc;
+            if (int rc = alloc(&tmp.stage[k], chunk_bytes_in)) return rc;
     }
     if (need_stats) {
         if (int rc = alloc(&tmp.row_acc, sizeof(double) * static_cast<size_t>(T) * F)) return rc;
@@ -187,8 +214,9 @@ int load_impl(pgti_ctx* c, const float* src, bool src_on_device, int64_t T, int3
     }
 
     // Sweep 0 moves the data (and sums values if statistics are wanted); sweep 1, only with
-    // statistics, sums squared deviations from the mean.  With bf16 storage the rounding happens
-    // in the last sweep, from the fp32 chunk, so statistics always see the caller's fp32 values.
+    // statistics, sums squared deviations from the mean.  Statistics always see fp32 values: with
+    // fp32 storage the finished resident rows, with bf16 storage the source chunk (the time-of-day
+    // channel synthesised on the fly); the bf16 rounding happens in the last sweep.
     const int sweeps = need_stats ? 2 : 1;
     for (int sweep = 0; sweep < sweeps; ++sweep) {
         const bool last_sweep = (sweep == sweeps - 1);
@@ -196,42 +224,62 @@ int load_impl(pgti_ctx* c, const float* src, bool src_on_device, int64_t T, int3
         bool slot_busy[2] = {false, false};
         for (int64_t row0 = 0; row0 < T; row0 += chunk_rows, slot ^= 1) {
             const int64_t rows = (T - row0 < chunk_rows) ? (T - row0) : chunk_rows;
-            const size_t off = static_cast<size_t>(row0) * R;
-            const size_t cnt = static_cast<size_t>(rows) * R;
-            const float* dev_chunk = nullptr;  // fp32 view of this chunk on the device
+            const size_t off = static_cast<size_t>(row0) * R, off_in = static_cast<size_t>(row0) * R_in;
+            const size_t cnt = static_cast<size_t>(rows) * R, cnt_in = static_cast<size_t>(rows) * R_in;
+            float* resident32 = static_cast<float*>(c->d_series) + off;  // meaningful for fp32 storage
 
-            if (src_on_device) {
-                dev_chunk = src + off;
-                if (storage == PGTI_F32 && sweep == 0)
-                    PGTI_HIP_TRY(hipMemcpyAsync(static_cast<float*>(c->d_series) + off, dev_chunk, cnt * 4,
-                                                hipMemcpyDeviceToDevice, ws));
-            } else if (storage == PGTI_F32 && sweep == 1) {
-                dev_chunk = static_cast<const float*>(c->d_series) + off;  // already resident
-            } else {
-                if (slot_busy[slot]) PGTI_HIP_TRY(hipEventSynchronize(tmp.done[slot]));
-                float* dst = (storage == PGTI_F32) ? static_cast<float*>(c->d_series) + off : tmp.stage[slot];
-                const void* from = src + off;
-                if (via_pinned_staging) {
-                    memcpy(tmp.pinned[slot], src + off, cnt * 4);
-                    from = tmp.pinned[slot];
+            // the source chunk on the device, when this sweep needs it
+            const float* src_chunk = nullptr;
+            if (sweep == 0 || storage == PGTI_BF16) {
+                if (src_on_device) {
+                    src_chunk = src + off_in;
+                } else {
+                    if (slot_busy[slot]) PGTI_HIP_TRY(hipEventSynchronize(tmp.done[slot]));
+                    float* dst = via_device_staging ? tmp.stage[slot] : resident32;
+                    const void* from = src + off_in;
+                    if (via_pinned_staging) {
+                        memcpy(tmp.pinned[slot], src + off_in, cnt_in * 4);
+                        from = tmp.pinned[slot];
+                    }
+                    PGTI_HIP_TRY(hipMemcpyAsync(dst, from, cnt_in * 4, hipMemcpyHostToDevice, ws));
+                    src_chunk = dst;
                 }
-                PGTI_HIP_TRY(hipMemcpyAsync(dst, from, cnt * 4, hipMemcpyHostToDevice, ws));
-                dev_chunk = dst;
             }
 
-            if (need_stats) {
-                const double* mean64 = (sweep == 1) ? tmp.stat64 : nullptr;
-                PGTI_HIP_TRY(launch_row_sums(dev_chunk, rows, N, F, row0, mean64, tmp.row_acc, ws));
+            if (storage == PGTI_F32) {
+                if (sweep == 0) {
+                    if (synth)
+                        PGTI_HIP_TRY(launch_assemble_rows(src_chunk, rows, N, F_in, F, row0, period, resident32, false, ws));
+                    else if (src_on_device)
+                        PGTI_HIP_TRY(hipMemcpyAsync(resident32, src_chunk, cnt * 4, hipMemcpyDeviceToDevice, ws));
+                }
+                if (need_stats)
+                    PGTI_HIP_TRY(launch_row_sums(resident32, rows, N, F, F, 0, row0, sweep == 1 ? tmp.stat64 : nullptr,
+                                                 tmp.row_acc, ws));
+            } else {
+                if (need_stats)
+                    PGTI_HIP_TRY(launch_row_sums(src_chunk, rows, N, F, F_in, period, row0,
+                                                 sweep == 1 ? tmp.stat64 : nullptr, tmp.row_acc, ws));
+                if (last_sweep) {
+                    uint16_t* resident16 = static_cast<uint16_t*>(c->d_series) + off;
+                    if (synth)
+                        PGTI_HIP_TRY(launch_assemble_rows(src_chunk, rows, N, F_in, F, row0, period, resident16, true, ws));
+                    else
+                        PGTI_HIP_TRY(launch_store_bf16(src_chunk, resident16, cnt, ws));
+                }
             }
-            if (storage == PGTI_BF16 && last_sweep)
-                PGTI_HIP_TRY(launch_store_bf16(dev_chunk, static_cast<uint16_t*>(c->d_series) + off, cnt, ws));
             PGTI_HIP_TRY(hipEventRecord(tmp.done[slot], ws));
             slot_busy[slot] = true;
         }
         if (need_stats) {
             // mean after sweep 0 (kept in fp64 on the device for sweep 1), std after sweep 1
             float* out32 = c->d_stats + (sweep == 0 ? 0 : F);
-            PGTI_HIP_TRY(launch_reduce_rows(tmp.row_acc, T, N, F, sweep == 1, tmp.stat64, out32, ws));
+            if (spec->stats_rule == PGTI_STATS_ALG1_TRAIN)
+                PGTI_HIP_TRY(launch_reduce_rows_alg1(tmp.row_acc, F, n_train, P,
+                                                     static_cast<double>(n_train) * P * static_cast<double>(R),
+                                                     sweep == 1, tmp.stat64, out32, ws));
+            else
+                PGTI_HIP_TRY(launch_reduce_rows(tmp.row_acc, T, N, F, sweep == 1, tmp.stat64, out32, ws));
         }
         PGTI_HIP_TRY(hipStreamSynchronize(ws));
     }
@@ -344,17 +392,45 @@ void pgti_destroy(pgti_ctx* c) {
     delete c;
 }
 
+static pgti_load_spec basic_spec(int64_t T, int32_t N, int32_t F, int32_t P, int32_t Q, int32_t B, pgti_dtype storage,
+                                 const float* mean, const float* std, int on_device) {
+    pgti_load_spec spec;
+    memset(&spec, 0, sizeof(spec));
+    spec.T = T;
+    spec.N = N;
+    spec.F_in = F;
+    spec.P = P;
+    spec.Q = Q;
+    spec.B = B;
+    spec.storage = storage;
+    spec.source_on_device = on_device;
+    spec.stats_rule = (mean || std) ? PGTI_STATS_GIVEN : PGTI_STATS_FEATURE_GLOBAL;
+    spec.train_fraction = 0.70;
+    spec.mean = mean;
+    spec.std = std;
+    return spec;
+}
+
 int pgti_load_series(pgti_ctx* c, const float* host_series, int64_t T, int32_t N, int32_t F, int32_t P,
                      int32_t Q, int32_t B, pgti_dtype storage, const float* mean, const float* std) {
     g_error[0] = 0;
-    return load_impl(c, host_series, false, T, N, F, P, Q, B, storage, mean, std);
+    if ((mean == nullptr) != (std == nullptr)) return fail(PGTI_ERR_ARG, "pass both mean and std, or neither");
+    const pgti_load_spec spec = basic_spec(T, N, F, P, Q, B, storage, mean, std, 0);
+    return load_impl(c, host_series, &spec);
 }
 
 int pgti_load_series_device(pgti_ctx* c, const float* device_series, int64_t T, int32_t N, int32_t F,
                             int32_t P, int32_t Q, int32_t B, pgti_dtype storage, const float* mean,
                             const float* std) {
     g_error[0] = 0;
-    return load_impl(c, device_series, true, T, N, F, P, Q, B, storage, mean, std);
+    if ((mean == nullptr) != (std == nullptr)) return fail(PGTI_ERR_ARG, "pass both mean and std, or neither");
+    const pgti_load_spec spec = basic_spec(T, N, F, P, Q, B, storage, mean, std, 1);
+    return load_impl(c, device_series, &spec);
+}
+
+int pgti_load_series_ex(pgti_ctx* c, const float* series, const pgti_load_spec* spec) {
+    g_error[0] = 0;
+    return load_impl(c, series, spec);
 }
 
 int pgti_get_stats(pgti_ctx* c, float* mean_out, float* std_out) {

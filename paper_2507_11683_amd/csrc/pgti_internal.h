@@ -85,8 +85,18 @@ hipError_t launch_store_bf16(const float* src, uint16_t* dst, size_t count, hipS
 // Per-row partial sums for the statistics.  row_acc is [rows_total][F] fp64 on the device; the
 // rows [row0, row0+rows) of it are written from `chunk` (fp32, rows x N x F, device).
 // mean64 == nullptr: sums of values; else sums of squared deviations from mean64[f] (device).
-hipError_t launch_row_sums(const float* chunk, int64_t rows, int32_t N, int32_t F, int64_t row0,
-                           const double* mean64, double* row_acc, hipStream_t s);
+// The chunk holds F_src <= F features per node; feature F_src (if F_src < F) is the time-of-day
+// channel (t mod period) / period, synthesised on the fly.
+hipError_t launch_row_sums(const float* chunk, int64_t rows, int32_t N, int32_t F, int32_t F_src, int32_t period,
+                           int64_t row0, const double* mean64, double* row_acc, hipStream_t s);
+// Algorithm 1's scalar statistic over the first n_train windows of x: weighted sum of the row sums
+// over count = n_train*P*N*F elements, written to all F entries of out64 / out32.
+hipError_t launch_reduce_rows_alg1(const double* row_acc, int32_t F, int64_t n_train, int32_t P, double count,
+                                   bool take_sqrt, double* out64, float* out32, hipStream_t s);
+// Resident rows [rows, N, F] (fp32 or bf16) from a source chunk [rows, N, F_src] plus the
+// time-of-day channel.
+hipError_t launch_assemble_rows(const float* src, int64_t rows, int32_t N, int32_t F_src, int32_t F, int64_t row0,
+                                int32_t period, void* dst, bool out_bf16, hipStream_t s);
 // Reduces row_acc over all T rows in a fixed order, divides by T*N; take_sqrt selects the
 // standard deviation.  out64 is [F] fp64 on the device, out32 [F] fp32 on the device.
 hipError_t launch_reduce_rows(const double* row_acc, int64_t T, int32_t N, int32_t F, bool take_sqrt,

@@ -48,6 +48,18 @@ class EpochSpec(ctypes.Structure):
                 ("seed", _u64), ("epoch", _u64), ("rank", _u32), ("world", _u32)]
 
 
+PGTI_STATS_GIVEN, PGTI_STATS_FEATURE_GLOBAL, PGTI_STATS_ALG1_TRAIN = 0, 1, 2
+
+
+class LoadSpec(ctypes.Structure):
+    """Mirror of pgti_load_spec."""
+    _fields_ = [("T", _i64), ("N", _i32), ("F_in", _i32), ("P", _i32), ("Q", _i32), ("B", _i32),
+                ("storage", _i32), ("source_on_device", _i32), ("stats_rule", _i32),
+                ("time_of_day_period", _i32), ("reserved", _i32), ("train_fraction", ctypes.c_double),
+                ("mean", _vp), ("std", _vp)]
+
+
+SIGNATURES["pgti_load_series_ex"] = (ctypes.c_int, [_vp, _vp, ctypes.POINTER(LoadSpec)])
 SIGNATURES["pgti_epoch_indices_ex"] = (ctypes.c_int, [_vp, ctypes.POINTER(EpochSpec), ctypes.POINTER(_i64)])
 
 _lib = None
@@ -148,6 +160,28 @@ class Context:
         mp, sp, _keep = _stats_ptrs(mean, std, F)
         fn = self._lib.pgti_load_series_device if on_device else self._lib.pgti_load_series
         _check(fn(self._h, ptr, T, N, F, P, Q, B, storage, mp, sp))
+        self.shape = (T, N, F, P, Q, B)
+
+    # -- pgti_load_series_ex ----------------------------------------------------------------------
+    def load_series_ex(self, series, P: int, Q: int, B: int, storage: int = PGTI_F32,
+                       stats_rule: int = PGTI_STATS_FEATURE_GLOBAL, time_of_day_period: int = 0,
+                       train_fraction: float = 0.70, mean=None, std=None) -> None:
+        """Load with on-device preprocessing: optional time-of-day feature and computed statistics."""
+        if isinstance(series, torch.Tensor):
+            if series.dtype != torch.float32 or not series.is_contiguous() or series.dim() != 3:
+                raise PgtiError(PGTI_ERR_ARG, "series must be a contiguous float32 [T, N, F] tensor")
+            T, N, F_in = series.shape
+            ptr, on_device = series.data_ptr(), series.is_cuda
+        else:
+            if series.dtype != np.float32 or not series.flags.c_contiguous or series.ndim != 3:
+                raise PgtiError(PGTI_ERR_ARG, "series must be a C-contiguous float32 [T, N, F] array")
+            T, N, F_in = series.shape
+            ptr, on_device = series.ctypes.data, False
+        F = F_in + (1 if time_of_day_period > 0 else 0)
+        mp, sp, _keep = _stats_ptrs(mean, std, F)
+        spec = LoadSpec(T, N, F_in, P, Q, B, storage, int(on_device), stats_rule, time_of_day_period, 0,
+                        train_fraction, mp, sp)
+        _check(self._lib.pgti_load_series_ex(self._h, ptr, ctypes.byref(spec)))
         self.shape = (T, N, F, P, Q, B)
 
     # -- pgti_get_stats ---------------------------------------------------------------------------

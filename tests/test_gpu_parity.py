@@ -523,6 +523,95 @@ def test_library_statistics(storage_name):
         _check_batches(ctx, _oracle_series(series, storage), storage, w.P, w.Q, w.B, got_m, got_s, share, [0, 17])
 
 
+def _ulp_close(a, b, ulps=1):
+    ia = int(np.float32(a).view(np.int32))
+    ib = int(np.float32(b).view(np.int32))
+    return abs(ia - ib) <= ulps
+
+
+@pytest.mark.parametrize("storage_name", ["f32", "bf16"])
+@pytest.mark.parametrize("source", ["host", "pinned", "device"])
+def test_on_device_time_of_day_feature(storage_name, source):
+    # stage 1 of the preprocessing on the device: the resident series gains (t mod period)/period
+    w = workloads.WORKLOADS["medium"]
+    full = workloads.make_series(w)                       # [T, N, 2]: speed, time of day
+    speed = np.ascontiguousarray(full[..., :1])           # what a caller would have on disk
+    want_series = oracle.add_time_of_day(speed, 288)
+    assert np.array_equal(want_series, full)
+    storage = pgti.PGTI_F32 if storage_name == "f32" else pgti.PGTI_BF16
+    src = {"host": speed, "pinned": torch.from_numpy(speed).pin_memory(),
+           "device": torch.from_numpy(speed).cuda()}[source]
+    mean, std = np.array([59.0, 0.0], np.float32), np.array([9.0, 1.0], np.float32)
+    with pgti.Context(0) as ctx:
+        ctx.load_series_ex(src, w.P, w.Q, w.B, storage, stats_rule=pgti.PGTI_STATS_GIVEN,
+                           time_of_day_period=288, mean=mean, std=std)
+        assert ctx.shape[2] == 2
+        ctx.epoch_indices(1, 0)
+        share = ctx.get_indices()
+        _check_batches(ctx, _oracle_series(want_series, storage), storage, w.P, w.Q, w.B, mean, std, share,
+                       [0, 100, ctx.num_batches() - 1])
+    # other periods and an odd node count
+    rng = np.random.default_rng(3)
+    small = rng.normal(5, 2, (100, 7, 2)).astype(np.float32)
+    with pgti.Context(0) as ctx:
+        ctx.load_series_ex(small, 3, 2, 4, storage, stats_rule=pgti.PGTI_STATS_GIVEN, time_of_day_period=24,
+                           mean=[0, 0, 0], std=[1, 1, 1])
+        ctx.epoch_indices_ex(pgti.PGTI_ORDER_SEQUENTIAL)
+        share = ctx.get_indices()
+        ws = oracle.add_time_of_day(small, 24)
+        _check_batches(ctx, _oracle_series(ws, storage), storage, 3, 2, 4, np.zeros(3, np.float32),
+                       np.ones(3, np.float32), share, range(ctx.num_batches()))
+
+
+@pytest.mark.parametrize("storage_name", ["f32", "bf16"])
+@pytest.mark.parametrize("fraction", [0.7, 0.5, 1.0])
+def test_on_device_algorithm1_statistics(storage_name, fraction):
+    # Algorithm 1's scalar mean/std over the training windows, with the time-of-day feature mixed in
+    # as the listing does.  fp64 accumulation on both sides in different orders: <= 1 fp32 ulp.
+    w = workloads.WORKLOADS["medium"]
+    full = workloads.make_series(w)
+    speed = np.ascontiguousarray(full[..., :1])
+    storage = pgti.PGTI_F32 if storage_name == "f32" else pgti.PGTI_BF16
+    want_m, want_s = oracle.alg1_train_stats_fraction(full, w.P, w.Q, fraction)
+    with pgti.Context(0) as ctx:
+        ctx.load_series_ex(speed, w.P, w.Q, w.B, storage, stats_rule=pgti.PGTI_STATS_ALG1_TRAIN,
+                           time_of_day_period=288, train_fraction=fraction)
+        got_m, got_s = ctx.get_stats()
+        assert got_m[0] == got_m[1] and got_s[0] == got_s[1]          # one scalar for every feature
+        assert _ulp_close(got_m[0], want_m) and _ulp_close(got_s[0], want_s), (got_m, want_m, got_s, want_s)
+        ctx.epoch_indices(2, 0)
+        share = ctx.get_indices()
+        _check_batches(ctx, _oracle_series(full, storage), storage, w.P, w.Q, w.B, got_m, got_s, share, [0, 7])
+    # without the synthesised feature, and per-feature global statistics with it
+    with pgti.Context(0) as ctx:
+        ctx.load_series_ex(full, w.P, w.Q, w.B, storage, stats_rule=pgti.PGTI_STATS_ALG1_TRAIN,
+                           train_fraction=fraction)
+        got_m, got_s = ctx.get_stats()
+        assert _ulp_close(got_m[1], want_m) and _ulp_close(got_s[0], want_s)
+        ctx.load_series_ex(speed, w.P, w.Q, w.B, storage, stats_rule=pgti.PGTI_STATS_FEATURE_GLOBAL,
+                           time_of_day_period=288)
+        got_m, got_s = ctx.get_stats()
+        om, os_ = oracle.series_stats(full)
+        assert all(_ulp_close(g, o) for g, o in zip(list(got_m) + list(got_s), list(om) + list(os_)))
+
+
+def test_load_ex_argument_errors():
+    series = np.zeros((40, 3, 1), np.float32)
+    with pgti.Context(0) as ctx:
+        for kwargs, status in [
+            (dict(stats_rule=pgti.PGTI_STATS_GIVEN), pgti.PGTI_ERR_ARG),                       # no mean/std
+            (dict(stats_rule=7), pgti.PGTI_ERR_ARG),
+            (dict(stats_rule=pgti.PGTI_STATS_ALG1_TRAIN, train_fraction=0.0), pgti.PGTI_ERR_ARG),
+            (dict(stats_rule=pgti.PGTI_STATS_ALG1_TRAIN, train_fraction=1.5), pgti.PGTI_ERR_ARG),
+            (dict(stats_rule=pgti.PGTI_STATS_ALG1_TRAIN, train_fraction=0.01), pgti.PGTI_ERR_RANGE),  # empty part
+            (dict(time_of_day_period=-1), pgti.PGTI_ERR_ARG),
+            (dict(stats_rule=pgti.PGTI_STATS_ALG1_TRAIN), pgti.PGTI_ERR_STATS),                # constant data
+        ]:
+            with pytest.raises(pgti.PgtiError) as e:
+                ctx.load_series_ex(series, 12, 12, 4, pgti.PGTI_F32, **kwargs)
+            assert e.value.status == status, kwargs
+
+
 def test_device_resident_source():
     w = workloads.WORKLOADS["tiny"]
     series = workloads.make_series(w)
