@@ -74,6 +74,9 @@ def _load():
         lib.oracle_build_batch.restype = ctypes.c_int
         lib.oracle_build_batch.argtypes = [vp, ctypes.c_int, i64, i64, i64, i64, i64, vp, vp, vp,
                                            i64, vp, vp]
+        lib.oracle_build_batch_bf16_out.restype = ctypes.c_int
+        lib.oracle_build_batch_bf16_out.argtypes = [vp, ctypes.c_int, i64, i64, i64, i64, i64, vp, vp, vp,
+                                                    i64, vp, vp]
         lib.oracle_alg1_preprocess.restype = ctypes.c_int
         lib.oracle_alg1_preprocess.argtypes = [vp, i64, i64, i64, i64, i64, vp, vp, vp, vp]
         lib.oracle_alg1_train_stats.restype = ctypes.c_int
@@ -215,6 +218,23 @@ def build_batch(series: np.ndarray, storage: int, P: int, Q: int, mean, std,
     y = np.empty((count, Q, N, F), dtype=np.float32)
     _check(_load().oracle_build_batch(_ptr(series), storage, T, N, F, P, Q, _ptr(mean), _ptr(std),
                                       _ptr(starts), count, _ptr(x), _ptr(y)), "build_batch")
+    return x, y
+
+
+def build_batch_bf16_out(series: np.ndarray, storage: int, P: int, Q: int, mean, std,
+                         starts) -> tuple[np.ndarray, np.ndarray]:
+    """Like build_batch, outputs as uint16 bf16 bit patterns."""
+    want = np.float32 if storage == F32 else np.uint16
+    if series.dtype != want or not series.flags.c_contiguous or series.ndim != 3:
+        raise ValueError("series must be a C-contiguous [T,N,F] array of the storage dtype")
+    T, N, F = series.shape
+    mean, std = _c(mean, np.float32), _c(std, np.float32)
+    starts = _c(starts, np.int32)
+    count = starts.shape[0]
+    x = np.empty((count, P, N, F), dtype=np.uint16)
+    y = np.empty((count, Q, N, F), dtype=np.uint16)
+    _check(_load().oracle_build_batch_bf16_out(_ptr(series), storage, T, N, F, P, Q, _ptr(mean), _ptr(std),
+                                               _ptr(starts), count, _ptr(x), _ptr(y)), "build_batch_bf16_out")
     return x, y
 
 

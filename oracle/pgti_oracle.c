@@ -284,6 +284,31 @@ int oracle_build_batch(const void* series, int storage, int64_t T, int64_t N, in
     return ORACLE_OK;
 }
 
+/* Same batch with bf16 outputs (this build's reduced-precision output option; the paper has
+ * none): every standardised fp32 value is rounded to bf16, nearest even, as its last step. */
+int oracle_build_batch_bf16_out(const void* series, int storage, int64_t T, int64_t N, int64_t F,
+                                int64_t P, int64_t Q, const float* mean, const float* std,
+                                const int32_t* starts, int64_t count, uint16_t* out_x,
+                                uint16_t* out_y) {
+    if (!series || !mean || !std || !starts || !out_x || !out_y) return ORACLE_ERR_ARG;
+    if (storage != 0 && storage != 1) return ORACLE_ERR_ARG;
+    int64_t n = oracle_window_count(T, P, Q);
+    for (int64_t j = 0; j < count; ++j) {
+        int64_t start = starts[j];
+        if (start < 0 || start >= n) return ORACLE_ERR_ARG;
+        for (int64_t p = 0; p < P + Q; ++p)
+            for (int64_t node = 0; node < N; ++node)
+                for (int64_t f = 0; f < F; ++f) {
+                    float v = oracle_standardize(series_at(series, storage, start + p, node, f, N, F),
+                                                 mean[f], std[f]);
+                    uint16_t b = oracle_bf16_from_f32(v);
+                    if (p < P) out_x[((j * P + p) * N + node) * F + f] = b;
+                    else out_y[((j * Q + (p - P)) * N + node) * F + f] = b;
+                }
+    }
+    return ORACLE_OK;
+}
+
 /* ------------------------------------------------------------------------------------------
  * Algorithm 1, the standard preprocessing, written as the paper lists it: visit every window,
  * append its x and its y (the slice one input length ahead), stack, then standardise both

@@ -559,3 +559,19 @@ def test_alg1_train_stats_other_fraction_and_weights():
         wmean = (wgt[:, None, None] * rows).sum() / (wgt.sum() * N * F)
         assert abs(mean - wmean) < 1e-9 and wgt.sum() == n_train * P
     assert oracle.alg1_train_stats(data, P, Q) == oracle.alg1_train_stats_fraction(data, P, Q, 0.70)
+
+
+def test_bf16_outputs_are_the_rounded_fp32_outputs():
+    torch = pytest.importorskip("torch")
+    rng = np.random.default_rng(41)
+    T, N, F, P, Q = 60, 9, 2, 5, 4
+    data = rng.normal(60, 9, (T, N, F)).astype(np.float32)
+    mean, std = oracle.series_stats(data)
+    starts = np.array([0, 17, 51, 3], np.int32)
+    x32, y32 = oracle.build_batch(data, oracle.F32, P, Q, mean, std, starts)
+    xb, yb = oracle.build_batch_bf16_out(data, oracle.F32, P, Q, mean, std, starts)
+    for got, ref in ((xb, x32), (yb, y32)):
+        lib = torch.from_numpy(ref.copy()).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
+        assert np.array_equal(got, lib)
+        widened = (got.astype(np.uint32) << 16).view(np.float32)
+        assert np.all(np.abs(widened - ref) <= np.abs(ref) * 2.0 ** -8)  # within half a bf16 ulp
