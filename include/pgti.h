@@ -226,6 +226,16 @@ int pgti_build_batch(pgti_ctx* c, int64_t batch_no, float* out_x, float* out_y, 
 int64_t pgti_build_batches(pgti_ctx* c, int64_t first_batch, int32_t k, float* out_x, float* out_y,
                            void* stream);
 
+/*
+ * Reduced-precision outputs (not in the paper; halves the bytes written per batch).  Same as
+ * pgti_build_batches, but every standardised fp32 value (Algorithm 1: (v - mu) / sigma, computed
+ * exactly as for the fp32 outputs) is rounded to bfloat16, nearest even, as the last step.
+ * out_x: DEVICE bf16 [k, B, P, N, F], out_y: DEVICE bf16 [k, B, Q, N, F] as 16-bit patterns,
+ * caller-owned, 16-byte aligned.  Returns the number of valid samples or a negative pgti_status.
+ */
+int64_t pgti_build_batches_bf16(pgti_ctx* c, int64_t first_batch, int32_t k, uint16_t* out_x,
+                                uint16_t* out_y, void* stream);
+
 /* Description of the last failure on the calling thread; "" if none.  Valid until the next
  * library call on this thread. */
 const char* pgti_last_error(void);

@@ -23,12 +23,15 @@
 //     about 15 issue slots; it matters when the stored type is bf16 (+7 % bandwidth) and is
 //     hidden behind memory time for fp32.  tests/fastdiv_model.c checks the identity on the host
 //     for every guarded dividend of hard divisors and for random divisors.
+#include <type_traits>
+
 #include "pgti_internal.h"
 
 namespace pgti {
 namespace {
 
 constexpr int kThreads = 256;
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x4_a4 __attribute__((ext_vector_type(4), aligned(4)));       // element-aligned quad
@@ -37,8 +40,8 @@ typedef uint32_t u32x2_a2 __attribute__((ext_vector_type(2), aligned(2)));    //
 struct GatherArgs {
     const void* series;     // resident [T, R], fp32 or bf16
     const int32_t* starts;  // this batch's starts
-    float* out_x;           // [count, P, R]
-    float* out_y;           // [count, Q, R]
+    void* out_x;            // [count, P, R], fp32 or bf16
+    void* out_y;            // [count, Q, R]
     int64_t R;
     int32_t last_start;    // n_windows - 1: starts are clamped to [0, last_start] before use
     uint32_t units_x;      // quads (or elements, scalar path) of one sample's x window
@@ -178,7 +181,29 @@ __device__ __forceinline__ f32x4 standardise_quad(f32x4 v, const QuadStats& t) {
 // 1 KiB of contiguous memory.  One quad per lane with many resident waves measured faster on
 // MI355X than deeper per-lane unrolling (more, shorter waves keep both the read and the write
 // stream busy); the division costs nothing at this rate.
-template <int STORE_BYTES, int FSTATIC, int THREADS, bool STREAM, bool FAST>
+// fp32 -> bf16, round to nearest even on the upper 16 bits; NaN keeps sign and upper payload and
+// gets the quiet bit (same rule as the bf16 storage rounding).
+__device__ __forceinline__ uint32_t bf16_bits(float v) {
+    const uint32_t u = __float_as_uint(v);
+    if ((u & 0x7FFFFFFFu) > 0x7F800000u) return (u >> 16) | 0x0040u;
+    return (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;
+}
+
+// Stores output quad number `index` of the array at `base`: 16 bytes of fp32, or 8 bytes of bf16 when
+// the outputs are emitted in bf16.  Non-temporal: written once, never re-read by these kernels.
+template <bool OUT_BF16>
+__device__ __forceinline__ void store_quad(void* base, size_t index, f32x4 r) {
+    if constexpr (OUT_BF16) {
+        u32x2 o;
+        o.x = bf16_bits(r.x) | (bf16_bits(r.y) << 16);
+        o.y = bf16_bits(r.z) | (bf16_bits(r.w) << 16);
+        __builtin_nontemporal_store(o, static_cast<u32x2*>(base) + index);
+    } else {
+        __builtin_nontemporal_store(r, static_cast<f32x4*>(base) + index);
+    }
+}
+
+template <int STORE_BYTES, int FSTATIC, int THREADS, bool STREAM, bool FAST, bool OUT_BF16>
 __global__ void __launch_bounds__(THREADS) gather_quads_kernel(GatherArgs a) {
     const uint32_t j = blockIdx.y;
     const uint32_t q = blockIdx.x * THREADS + threadIdx.x;
@@ -190,11 +215,10 @@ __global__ void __launch_bounds__(THREADS) gather_quads_kernel(GatherArgs a) {
     if (q >= a.units_total) return;
     const f32x4 v = load_quad<STORE_BYTES, STREAM>(a.series, e0 + 4ll * q);
     const f32x4 r = standardise_quad<FAST>(v, t);
-    f32x4* dst = (q < a.units_x)
-                     ? reinterpret_cast<f32x4*>(a.out_x) + static_cast<size_t>(j) * a.units_x + q
-                     : reinterpret_cast<f32x4*>(a.out_y) +
-                           static_cast<size_t>(j) * (a.units_total - a.units_x) + (q - a.units_x);
-    __builtin_nontemporal_store(r, dst);  // written once, never re-read by this kernel
+    if (q < a.units_x)
+        store_quad<OUT_BF16>(a.out_x, static_cast<size_t>(j) * a.units_x + q, r);
+    else
+        store_quad<OUT_BF16>(a.out_y, static_cast<size_t>(j) * (a.units_total - a.units_x) + (q - a.units_x), r);
 }
 
 // Row-centric variant for batches of CONSECUTIVE starts (sequential and batch-level-shuffled
@@ -213,7 +237,7 @@ struct RowArgs {
     uint32_t row_quads;    // R / 4
 };
 
-template <int STORE_BYTES, int FSTATIC, int THREADS, bool STREAM, bool FAST>
+template <int STORE_BYTES, int FSTATIC, int THREADS, bool STREAM, bool FAST, bool OUT_BF16>
 __global__ void __launch_bounds__(THREADS) gather_rows_kernel(RowArgs a) {
     const uint32_t run = blockIdx.z, rr = blockIdx.y;
     const uint32_t q = blockIdx.x * THREADS + threadIdx.x;  // quad inside the row
@@ -232,20 +256,17 @@ __global__ void __launch_bounds__(THREADS) gather_rows_kernel(RowArgs a) {
 
     const uint32_t j_lo = (rr >= a.PQ - 1) ? rr - (a.PQ - 1) : 0u;
     const uint32_t j_hi = (rr < run_len - 1) ? rr : run_len - 1;
-    f32x4* const x = reinterpret_cast<f32x4*>(a.g.out_x);
-    f32x4* const y = reinterpret_cast<f32x4*>(a.g.out_y);
     const uint32_t Q = a.PQ - a.P;
     for (uint32_t j = j_lo; j <= j_hi; ++j) {
         const uint32_t p = rr - j;  // step of sample j that shows this row
         const size_t sample = first_sample + j;
-        f32x4* dst = (p < a.P) ? x + (sample * a.P + p) * a.row_quads + q
-                               : y + (sample * Q + (p - a.P)) * a.row_quads + q;
-        __builtin_nontemporal_store(r, dst);
+        if (p < a.P) store_quad<OUT_BF16>(a.g.out_x, (sample * a.P + p) * a.row_quads + q, r);
+        else store_quad<OUT_BF16>(a.g.out_y, (sample * Q + (p - a.P)) * a.row_quads + q, r);
     }
 }
 
 // Any geometry (P*R or Q*R not a multiple of 4): one element per thread.
-template <int STORE_BYTES>
+template <int STORE_BYTES, bool OUT_BF16>
 __global__ void __launch_bounds__(kThreads) gather_scalar_kernel(GatherArgs a) {
     const uint32_t j = blockIdx.y;
     const int64_t e0 = span_offset(a, j);
@@ -259,65 +280,107 @@ __global__ void __launch_bounds__(kThreads) gather_scalar_kernel(GatherArgs a) {
     }
     const uint32_t f = e % a.F;
     const float r = (v - a.d_mean[f]) / a.d_std[f];
-    float* dst = (e < a.units_x)
-                     ? a.out_x + static_cast<size_t>(j) * a.units_x + e
-                     : a.out_y + static_cast<size_t>(j) * (a.units_total - a.units_x) + (e - a.units_x);
-    *dst = r;
+    const bool in_x = e < a.units_x;
+    const size_t at = in_x ? static_cast<size_t>(j) * a.units_x + e
+                           : static_cast<size_t>(j) * (a.units_total - a.units_x) + (e - a.units_x);
+    void* base = in_x ? a.out_x : a.out_y;
+    if constexpr (OUT_BF16) static_cast<uint16_t*>(base)[at] = static_cast<uint16_t>(bf16_bits(r));
+    else static_cast<float*>(base)[at] = r;
 }
+
+// Turns run-time switches into template arguments: fn receives std::true_type or std::false_type.
+template <typename Fn>
+void with_bool(bool v, Fn&& fn) {
+    if (v) fn(std::true_type{});
+    else fn(std::false_type{});
+}
+
+struct Switches {
+    bool stream_loads, fast_divide, out_bf16;
+};
 
 template <int STORE_BYTES, int FSTATIC, int THREADS>
-void launch_quads_t(const GatherArgs& a, int32_t count, bool stream_loads, bool fast, hipStream_t s) {
+void launch_quads_t(const GatherArgs& a, int32_t count, Switches sw, hipStream_t s) {
     dim3 grid((a.units_total + THREADS - 1) / THREADS, count), block(THREADS);
-    if (stream_loads) {
-        if (fast) hipLaunchKernelGGL((gather_quads_kernel<STORE_BYTES, FSTATIC, THREADS, true, true>), grid, block, 0, s, a);
-        else hipLaunchKernelGGL((gather_quads_kernel<STORE_BYTES, FSTATIC, THREADS, true, false>), grid, block, 0, s, a);
-    } else {
-        if (fast) hipLaunchKernelGGL((gather_quads_kernel<STORE_BYTES, FSTATIC, THREADS, false, true>), grid, block, 0, s, a);
-        else hipLaunchKernelGGL((gather_quads_kernel<STORE_BYTES, FSTATIC, THREADS, false, false>), grid, block, 0, s, a);
-    }
+    with_bool(sw.stream_loads, [&](auto st) {
+        with_bool(sw.fast_divide, [&](auto fa) {
+            with_bool(sw.out_bf16, [&](auto ob) {
+                hipLaunchKernelGGL((gather_quads_kernel<STORE_BYTES, FSTATIC, THREADS, decltype(st)::value,
+                                                        decltype(fa)::value, decltype(ob)::value>),
+                                   grid, block, 0, s, a);
+            });
+        });
+    });
 }
 
 template <int STORE_BYTES, int FSTATIC>
-void launch_quads(const GatherArgs& a, int32_t count, bool stream_loads, bool fast, hipStream_t s) {
+void launch_quads(const GatherArgs& a, int32_t count, Switches sw, hipStream_t s) {
     // 512-lane workgroups for long samples (fewer workgroups to dispatch), 256 otherwise.
-    if (a.units_total >= 32768u) launch_quads_t<STORE_BYTES, FSTATIC, 512>(a, count, stream_loads, fast, s);
-    else launch_quads_t<STORE_BYTES, FSTATIC, 256>(a, count, stream_loads, fast, s);
-}
-
-template <int STORE_BYTES>
-void launch_quads_f(const GatherArgs& a, int32_t count, bool stream_loads, bool fast, hipStream_t s) {
-    if (a.F == 1) launch_quads<STORE_BYTES, 1>(a, count, stream_loads, fast, s);
-    else if (a.F == 2) launch_quads<STORE_BYTES, 2>(a, count, stream_loads, fast, s);
-    else if (a.F == 4) launch_quads<STORE_BYTES, 4>(a, count, stream_loads, fast, s);
-    else launch_quads<STORE_BYTES, 0>(a, count, stream_loads, fast, s);
+    if (a.units_total >= 32768u) launch_quads_t<STORE_BYTES, FSTATIC, 512>(a, count, sw, s);
+    else launch_quads_t<STORE_BYTES, FSTATIC, 256>(a, count, sw, s);
 }
 
 template <int STORE_BYTES, int FSTATIC>
-void launch_rows(const RowArgs& a, bool stream_loads, bool fast, hipStream_t s) {
+void launch_rows(const RowArgs& a, Switches sw, hipStream_t s) {
     constexpr int kT = 256;
     const uint32_t runs = (a.count + a.B - 1) / a.B;
     dim3 grid((a.row_quads + kT - 1) / kT, a.B + a.PQ - 1, runs), block(kT);
-    if (stream_loads) {
-        if (fast) hipLaunchKernelGGL((gather_rows_kernel<STORE_BYTES, FSTATIC, kT, true, true>), grid, block, 0, s, a);
-        else hipLaunchKernelGGL((gather_rows_kernel<STORE_BYTES, FSTATIC, kT, true, false>), grid, block, 0, s, a);
-    } else {
-        if (fast) hipLaunchKernelGGL((gather_rows_kernel<STORE_BYTES, FSTATIC, kT, false, true>), grid, block, 0, s, a);
-        else hipLaunchKernelGGL((gather_rows_kernel<STORE_BYTES, FSTATIC, kT, false, false>), grid, block, 0, s, a);
-    }
+    with_bool(sw.stream_loads, [&](auto st) {
+        with_bool(sw.fast_divide, [&](auto fa) {
+            with_bool(sw.out_bf16, [&](auto ob) {
+                hipLaunchKernelGGL((gather_rows_kernel<STORE_BYTES, FSTATIC, kT, decltype(st)::value,
+                                                       decltype(fa)::value, decltype(ob)::value>),
+                                   grid, block, 0, s, a);
+            });
+        });
+    });
+}
+
+// Picks the feature pattern: 1, 2 and 4 features are compile-time patterns, anything else generic.
+template <int STORE_BYTES, typename Fn>
+void with_feature_pattern(uint32_t F, Fn&& fn) {
+    if (F == 1) fn(std::integral_constant<int, 1>{});
+    else if (F == 2) fn(std::integral_constant<int, 2>{});
+    else if (F == 4) fn(std::integral_constant<int, 4>{});
+    else fn(std::integral_constant<int, 0>{});
 }
 
 template <int STORE_BYTES>
-void launch_rows_f(const RowArgs& a, bool stream_loads, bool fast, hipStream_t s) {
-    if (a.g.F == 1) launch_rows<STORE_BYTES, 1>(a, stream_loads, fast, s);
-    else if (a.g.F == 2) launch_rows<STORE_BYTES, 2>(a, stream_loads, fast, s);
-    else if (a.g.F == 4) launch_rows<STORE_BYTES, 4>(a, stream_loads, fast, s);
-    else launch_rows<STORE_BYTES, 0>(a, stream_loads, fast, s);
+void launch_for_storage(const pgti_ctx* c, GatherArgs& a, int32_t count, bool out_bf16, hipStream_t s) {
+    const int64_t ex = static_cast<int64_t>(c->P) * c->R, et = static_cast<int64_t>(c->P + c->Q) * c->R;
+    const bool big_series = c->series_bytes > (256ull << 20);
+    if (c->share_consecutive && c->R % 4 == 0 && c->B + c->P + c->Q - 1 <= 65535 &&
+        (count + c->B - 1) / c->B <= 65535) {
+        // Batches of consecutive starts: fetch every source row once (d_starts is batch aligned).
+        RowArgs ra{};
+        ra.g = a;
+        ra.B = static_cast<uint32_t>(c->B);
+        ra.count = static_cast<uint32_t>(count);
+        ra.P = static_cast<uint32_t>(c->P);
+        ra.PQ = static_cast<uint32_t>(c->P + c->Q);
+        ra.row_quads = static_cast<uint32_t>(c->R / 4);
+        const Switches sw{big_series, c->fast_divide, out_bf16};
+        with_feature_pattern<STORE_BYTES>(a.F, [&](auto fs) { launch_rows<STORE_BYTES, decltype(fs)::value>(ra, sw, s); });
+    } else if (c->path == GatherPath::kQuads) {
+        a.units_x = static_cast<uint32_t>(ex / 4);
+        a.units_total = static_cast<uint32_t>(et / 4);
+        // Non-temporal loads once the series cannot live in the 256 MB last-level cache anyway
+        // (with consecutive starts the rows are re-read by neighbouring samples: keep them cached).
+        const Switches sw{big_series && !c->share_consecutive, c->fast_divide, out_bf16};
+        with_feature_pattern<STORE_BYTES>(a.F, [&](auto fs) { launch_quads<STORE_BYTES, decltype(fs)::value>(a, count, sw, s); });
+    } else {
+        a.units_x = static_cast<uint32_t>(ex);
+        a.units_total = static_cast<uint32_t>(et);
+        dim3 grid((a.units_total + kThreads - 1) / kThreads, count);
+        if (out_bf16) hipLaunchKernelGGL((gather_scalar_kernel<STORE_BYTES, true>), grid, dim3(kThreads), 0, s, a);
+        else hipLaunchKernelGGL((gather_scalar_kernel<STORE_BYTES, false>), grid, dim3(kThreads), 0, s, a);
+    }
 }
 
 }  // namespace
 
-hipError_t launch_batch_gather(const pgti_ctx* c, const int32_t* d_starts, int32_t count,
-                               float* out_x, float* out_y, hipStream_t s) {
+hipError_t launch_batch_gather(const pgti_ctx* c, const int32_t* d_starts, int32_t count, void* out_x, void* out_y,
+                               bool out_bf16, hipStream_t s) {
     GatherArgs a{};
     a.series = c->d_series;
     a.starts = d_starts;
@@ -334,37 +397,8 @@ hipError_t launch_batch_gather(const pgti_ctx* c, const int32_t* d_starts, int32
     a.d_mean = c->d_stats;
     a.d_std = c->d_stats + c->F;
     a.d_recip = c->d_stats + 2 * c->F;
-    const int64_t ex = static_cast<int64_t>(c->P) * c->R, et = static_cast<int64_t>(c->P + c->Q) * c->R;
-    const bool big_series = c->series_bytes > (256ull << 20);
-    if (c->share_consecutive && c->R % 4 == 0 && c->B + c->P + c->Q - 1 <= 65535 &&
-        (count + c->B - 1) / c->B <= 65535) {
-        // Batches of consecutive starts: fetch every source row once (d_starts is batch aligned).
-        RowArgs ra{};
-        ra.g = a;
-        ra.B = static_cast<uint32_t>(c->B);
-        ra.count = static_cast<uint32_t>(count);
-        ra.P = static_cast<uint32_t>(c->P);
-        ra.PQ = static_cast<uint32_t>(c->P + c->Q);
-        ra.row_quads = static_cast<uint32_t>(c->R / 4);
-        if (c->storage == PGTI_F32) launch_rows_f<4>(ra, big_series, c->fast_divide, s);
-        else launch_rows_f<2>(ra, big_series, c->fast_divide, s);
-    } else if (c->path == GatherPath::kQuads) {
-        a.units_x = static_cast<uint32_t>(ex / 4);
-        a.units_total = static_cast<uint32_t>(et / 4);
-        // Non-temporal loads once the series cannot live in the 256 MB last-level cache anyway.
-        // (with consecutive starts the rows are re-read by neighbouring samples: keep them cached)
-        const bool stream_loads = big_series && !c->share_consecutive;
-        if (c->storage == PGTI_F32) launch_quads_f<4>(a, count, stream_loads, c->fast_divide, s);
-        else launch_quads_f<2>(a, count, stream_loads, c->fast_divide, s);
-    } else {
-        a.units_x = static_cast<uint32_t>(ex);
-        a.units_total = static_cast<uint32_t>(et);
-        dim3 grid((a.units_total + kThreads - 1) / kThreads, count);
-        if (c->storage == PGTI_F32)
-            hipLaunchKernelGGL((gather_scalar_kernel<4>), grid, dim3(kThreads), 0, s, a);
-        else
-            hipLaunchKernelGGL((gather_scalar_kernel<2>), grid, dim3(kThreads), 0, s, a);
-    }
+    if (c->storage == PGTI_F32) launch_for_storage<4>(c, a, count, out_bf16, s);
+    else launch_for_storage<2>(c, a, count, out_bf16, s);
     return hipGetLastError();
 }
 

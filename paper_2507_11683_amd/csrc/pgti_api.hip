@@ -537,7 +537,8 @@ int64_t pgti_num_batches(pgti_ctx* c) {
 }
 
 // Common part of the single- and multi-batch builds: checks, stream ordering, launches.
-static int64_t build_range(pgti_ctx* c, int64_t first_batch, int64_t k, float* out_x, float* out_y, void* stream) {
+static int64_t build_range(pgti_ctx* c, int64_t first_batch, int64_t k, void* out_x, void* out_y, bool out_bf16,
+                           void* stream) {
     if (!c) return fail(PGTI_ERR_ARG, "null context");
     if (!c->loaded) return fail(PGTI_ERR_STATE, "no series loaded");
     if (!c->have_share) return fail(PGTI_ERR_STATE, "no epoch indices generated");
@@ -580,21 +581,29 @@ static int64_t build_range(pgti_ctx* c, int64_t first_batch, int64_t k, float* o
     const int64_t max_part = (65535 / c->B) * static_cast<int64_t>(c->B);  // whole batches per launch
     for (int64_t done = 0; done < count; done += max_part) {
         const int32_t part = static_cast<int32_t>((count - done < max_part) ? (count - done) : max_part);
-        PGTI_HIP_TRY(launch_batch_gather(c, c->d_share + first + done, part, out_x + done * x_stride,
-                                         out_y + done * y_stride, s));
+        const size_t out_elem = out_bf16 ? 2 : 4;
+        PGTI_HIP_TRY(launch_batch_gather(c, c->d_share + first + done, part,
+                                         static_cast<char*>(out_x) + done * x_stride * out_elem,
+                                         static_cast<char*>(out_y) + done * y_stride * out_elem, out_bf16, s));
     }
     return count;
 }
 
 int pgti_build_batch(pgti_ctx* c, int64_t batch_no, float* out_x, float* out_y, void* stream) {
     g_error[0] = 0;
-    return static_cast<int>(build_range(c, batch_no, 1, out_x, out_y, stream));
+    return static_cast<int>(build_range(c, batch_no, 1, out_x, out_y, false, stream));
 }
 
 int64_t pgti_build_batches(pgti_ctx* c, int64_t first_batch, int32_t k, float* out_x, float* out_y,
                            void* stream) {
     g_error[0] = 0;
-    return build_range(c, first_batch, k, out_x, out_y, stream);
+    return build_range(c, first_batch, k, out_x, out_y, false, stream);
+}
+
+int64_t pgti_build_batches_bf16(pgti_ctx* c, int64_t first_batch, int32_t k, uint16_t* out_x, uint16_t* out_y,
+                                void* stream) {
+    g_error[0] = 0;
+    return build_range(c, first_batch, k, out_x, out_y, true, stream);
 }
 
 const char* pgti_last_error(void) { return g_error; }

@@ -120,8 +120,9 @@ hipError_t launch_expand_batches(const int32_t* order, uint32_t n_full, uint32_t
                                  uint32_t len, hipStream_t s);
 
 // ---- batch_gather.hip -----------------------------------------------------------------------
-// Enqueues the fused gather + standardise of `count` samples whose starts are d_starts[0..count).
-hipError_t launch_batch_gather(const pgti_ctx* c, const int32_t* d_starts, int32_t count,
-                               float* out_x, float* out_y, hipStream_t s);
+// Enqueues the fused gather + standardise of `count` samples whose starts are d_starts[0..count);
+// outputs fp32, or bf16 (out_bf16) rounded to nearest even from the fp32 result.
+hipError_t launch_batch_gather(const pgti_ctx* c, const int32_t* d_starts, int32_t count, void* out_x, void* out_y,
+                               bool out_bf16, hipStream_t s);
 
 }  // namespace pgti

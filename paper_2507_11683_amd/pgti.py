@@ -36,6 +36,7 @@ SIGNATURES = {
     "pgti_num_batches": (_i64, [_vp]),
     "pgti_build_batch": (ctypes.c_int, [_vp, _i64, _vp, _vp, _vp]),
     "pgti_build_batches": (_i64, [_vp, _i64, _i32, _vp, _vp, _vp]),
+    "pgti_build_batches_bf16": (_i64, [_vp, _i64, _i32, _vp, _vp, _vp]),
     "pgti_last_error": (ctypes.c_char_p, []),
 }
 
@@ -242,6 +243,22 @@ class Context:
                 raise PgtiError(PGTI_ERR_ARG, f"{name} holds fewer than k*B*{steps}*N*F elements")
         return _check(self._lib.pgti_build_batches(self._h, first_batch, k, out_x.data_ptr(),
                                                    out_y.data_ptr(), _stream_handle(stream)))
+
+    # -- pgti_build_batches_bf16 ------------------------------------------------------------------
+    def build_batches_bf16(self, first_batch: int, k: int, out_x: torch.Tensor, out_y: torch.Tensor,
+                           stream=None) -> int:
+        """Like build_batches with bfloat16 outputs out_x[k,B,P,N,F], out_y[k,B,Q,N,F]."""
+        T, N, F, P, Q, B = self.shape
+        for t, steps, name in ((out_x, P, "out_x"), (out_y, Q, "out_y")):
+            if not (t.is_cuda and t.dtype == torch.bfloat16 and t.is_contiguous()):
+                raise PgtiError(PGTI_ERR_ARG, f"{name} must be a contiguous bfloat16 CUDA tensor")
+            if t.numel() < max(k, 0) * B * steps * N * F:
+                raise PgtiError(PGTI_ERR_ARG, f"{name} holds fewer than k*B*{steps}*N*F elements")
+        return _check(self._lib.pgti_build_batches_bf16(self._h, first_batch, k, out_x.data_ptr(),
+                                                        out_y.data_ptr(), _stream_handle(stream)))
+
+    def build_batches_bf16_raw(self, first_batch: int, k: int, x_ptr: int, y_ptr: int, stream_handle: int) -> int:
+        return self._lib.pgti_build_batches_bf16(self._h, first_batch, k, x_ptr, y_ptr, stream_handle)
 
     def build_batches_raw(self, first_batch: int, k: int, x_ptr: int, y_ptr: int, stream_handle: int) -> int:
         return self._lib.pgti_build_batches(self._h, first_batch, k, x_ptr, y_ptr, stream_handle)

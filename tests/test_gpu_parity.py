@@ -523,6 +523,67 @@ def test_library_statistics(storage_name):
         _check_batches(ctx, _oracle_series(series, storage), storage, w.P, w.Q, w.B, got_m, got_s, share, [0, 17])
 
 
+BF16_OUT_GEOMETRIES = [GEOMETRIES[0], GEOMETRIES[2], GEOMETRIES[4], GEOMETRIES[7], GEOMETRIES[8], GEOMETRIES[9],
+                       ROW_GEOMETRIES[0], ROW_GEOMETRIES[2], ROW_GEOMETRIES[5], ROW_GEOMETRIES[6]]
+
+
+@pytest.mark.parametrize("order_name", list(ORDERS))
+@pytest.mark.parametrize("storage_name", ["f32", "bf16"])
+@pytest.mark.parametrize("geom", BF16_OUT_GEOMETRIES, ids=lambda g: "T%d_N%d_F%d_P%d_Q%d_B%d" % g)
+def test_bf16_outputs(geom, storage_name, order_name):
+    # Tolerance stated for bf16 outputs is 1 bf16 ulp; the kernel rounds the same fp32 value the
+    # oracle rounds, with the same rule, so the comparison is in fact bit for bit (NaN as NaN).
+    T, N, F, P, Q, B = geom
+    rng = np.random.default_rng(sum((i + 5) * v for i, v in enumerate(geom)))
+    series = _special_series(rng, T, N, F)
+    mean = rng.normal(40, 10, F).astype(np.float32)
+    std = rng.uniform(0.3, 25, F).astype(np.float32)
+    storage = pgti.PGTI_F32 if storage_name == "f32" else pgti.PGTI_BF16
+    ser_o = _oracle_series(series, storage)
+    canary = 0x1234
+    with pgti.Context(0) as ctx:
+        ctx.load_series(series, P, Q, B, storage, mean, std)
+        ctx.epoch_indices_ex(ORDERS[order_name], seed=6, epoch=1)
+        share = ctx.get_indices()
+        nb = ctx.num_batches()
+        for fb, k in {(0, nb), (nb - 1, 1), (nb // 2, max(1, nb // 3))}:
+            x = torch.full((k, B, P, N, F), canary, dtype=torch.int16, device="cuda").view(torch.bfloat16)
+            y = torch.full((k, B, Q, N, F), canary, dtype=torch.int16, device="cuda").view(torch.bfloat16)
+            total = ctx.build_batches_bf16(fb, k, x, y)
+            torch.cuda.synchronize()
+            starts = share[fb * B:(fb + k) * B]
+            assert total == len(starts)
+            wx, wy = oracle.build_batch_bf16_out(ser_o, storage, P, Q, mean, std, starts)
+            gx = x.view(torch.int16).cpu().numpy().view(np.uint16).reshape(k * B, P, N, F)
+            gy = y.view(torch.int16).cpu().numpy().view(np.uint16).reshape(k * B, Q, N, F)
+            for got, want in ((gx[:total], wx), (gy[:total], wy)):
+                same = got == want
+                nan_g = ((got & 0x7F80) == 0x7F80) & ((got & 0x7F) != 0)
+                nan_w = ((want & 0x7F80) == 0x7F80) & ((want & 0x7F) != 0)
+                assert np.all(same | (nan_g & nan_w)), (fb, k, np.flatnonzero(~(same | (nan_g & nan_w)))[:4])
+            assert np.all(gx[total:] == canary) and np.all(gy[total:] == canary)
+
+
+def test_bf16_outputs_statewide_sampled(statewide_series):
+    w = workloads.WORKLOADS["statewide"]
+    mean, std = _sampled_stats(statewide_series)
+    k = 4
+    with pgti.Context(0) as ctx:
+        ctx.load_series(statewide_series, w.P, w.Q, w.B, pgti.PGTI_F32, mean, std)
+        ctx.epoch_indices(w.seed, 0)
+        share = ctx.get_indices()
+        x = torch.empty((k, w.B, w.P, w.N, w.F), dtype=torch.bfloat16, device="cuda")
+        y = torch.empty((k, w.B, w.Q, w.N, w.F), dtype=torch.bfloat16, device="cuda")
+        for first in (0, 2000):
+            total = ctx.build_batches_bf16(first, k, x, y)
+            torch.cuda.synchronize()
+            starts = share[first * w.B:(first + k) * w.B]
+            wx, wy = oracle.build_batch_bf16_out(statewide_series, oracle.F32, w.P, w.Q, mean, std, starts)
+            gx = x.view(torch.int16).cpu().numpy().view(np.uint16).reshape(k * w.B, w.P, w.N, w.F)[:total]
+            gy = y.view(torch.int16).cpu().numpy().view(np.uint16).reshape(k * w.B, w.Q, w.N, w.F)[:total]
+            assert np.array_equal(gx, wx) and np.array_equal(gy, wy), first
+
+
 def _ulp_close(a, b, ulps=1):
     ia = int(np.float32(a).view(np.int32))
     ib = int(np.float32(b).view(np.int32))
