@@ -36,6 +36,8 @@ def parse_args():
                     help="output buffer sets rotated (0 = enough to exceed the 256 MB last-level cache)")
     ap.add_argument("--order", default="shuffle", choices=["shuffle", "sequential", "batch_shuffle"],
                     help="epoch order (the headline metric is the global shuffle)")
+    ap.add_argument("--out-dtype", default="f32", choices=["f32", "bf16"],
+                    help="output element type (the headline metric uses fp32 outputs)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-batches", type=int, default=0, help="oracle batches on one core (0 = auto)")
     ap.add_argument("--roofline-launches", type=int, default=4096,
@@ -164,8 +166,12 @@ def main():
 
     n_share = gen_indices(w.epochs[0])
     nb = ctx.num_batches()
-    batch_bytes = w.B * w.bytes_per_snapshot()            # algorithmic read + write of a full batch
-    out_bytes = w.B * (w.P + w.Q) * w.N * w.F * 4         # x + y of one batch
+    out_elem = 4 if args.out_dtype == "f32" else 2
+    out_torch = torch.float32 if args.out_dtype == "f32" else torch.bfloat16
+    bps = w.bytes_per_snapshot(out_elem)                  # algorithmic bytes per snapshot
+    batch_bytes = w.B * bps                               # algorithmic read + write of a full batch
+    out_bytes = w.B * (w.P + w.Q) * w.N * w.F * out_elem  # x + y of one batch
+    build_raw = ctx.build_batches_raw if args.out_dtype == "f32" else ctx.build_batches_bf16_raw
     k = args.batches_per_launch or max(1, min(nb, -(-(512 << 20) // batch_bytes)))
     if not args.batches_per_launch and args.order != "shuffle" and w.series_bytes_f32 > (256 << 20):
         k = 1  # consecutive starts, write-bound row-centric kernel: measured fastest at one batch per launch
@@ -173,14 +179,14 @@ def main():
 
     # ---- output buffers: rotate enough sets that writes cannot sit in the 256 MB last-level cache --
     sets = args.out_pairs or min(64, max(3, -(-(768 << 20) // (k * out_bytes))))
-    xs = [torch.empty((k, w.B, w.P, w.N, w.F), dtype=torch.float32, device="cuda") for _ in range(sets)]
-    ys = [torch.empty((k, w.B, w.Q, w.N, w.F), dtype=torch.float32, device="cuda") for _ in range(sets)]
+    xs = [torch.empty((k, w.B, w.P, w.N, w.F), dtype=out_torch, device="cuda") for _ in range(sets)]
+    ys = [torch.empty((k, w.B, w.Q, w.N, w.F), dtype=out_torch, device="cuda") for _ in range(sets)]
     xp, yp = [t.data_ptr() for t in xs], [t.data_ptr() for t in ys]
     stream = torch.cuda.current_stream()
     sh = stream.cuda_stream
     steps = args.steps or nb * len(w.epochs)
 
-    x_batch_bytes, y_batch_bytes = w.B * w.P * w.N * w.F * 4, w.B * w.Q * w.N * w.F * 4
+    x_batch_bytes, y_batch_bytes = w.B * w.P * w.N * w.F * out_elem, w.B * w.Q * w.N * w.F * out_elem
 
     def out_ptrs(launch: int, per_launch: int):
         """Rotates launches over every slot of every set (per_launch consecutive slots each)."""
@@ -198,7 +204,7 @@ def main():
             if b == 0:
                 gen_indices(w.epochs[0] + e)  # consecutive epochs
             kk = min(per_launch, nb - b, n_steps - i)
-            rc = ctx.build_batches_raw(b, kk, *out_ptrs(launch, per_launch), sh)
+            rc = build_raw(b, kk, *out_ptrs(launch, per_launch), sh)
             if rc < 0:
                 raise RuntimeError(pgti.last_error())
             snaps += rc
@@ -226,18 +232,18 @@ def main():
         reps = max(1, min(64, args.roofline_launches // per_epoch))
         ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         for l in range(min(per_epoch, 16)):
-            ctx.build_batches_raw(l * per_launch, per_launch, *out_ptrs(l, per_launch), sh)
+            build_raw(l * per_launch, per_launch, *out_ptrs(l, per_launch), sh)
         torch.cuda.synchronize()
         ev0.record(stream)
         n = 0
         for _ in range(reps):
             for l in range(per_epoch):
-                ctx.build_batches_raw(l * per_launch, per_launch, *out_ptrs(n, per_launch), sh)
+                build_raw(l * per_launch, per_launch, *out_ptrs(n, per_launch), sh)
                 n += 1
         ev1.record(stream)
         torch.cuda.synchronize()
         avg_s = ev0.elapsed_time(ev1) * 1e-3 / n
-        nbytes = per_launch * min(w.B, n_share) * w.bytes_per_snapshot()
+        nbytes = per_launch * min(w.B, n_share) * bps
         return {"launches": n, "avg_launch_us": avg_s * 1e6, "algorithmic_bytes_per_launch": nbytes,
                 "achieved": nbytes / avg_s / 1e9, "batches_per_launch": per_launch}
 
@@ -271,14 +277,15 @@ def main():
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
-        "dtype": "f32",
+        "dtype": "f32",  # arithmetic type: subtraction and division are binary32 whatever is stored or emitted
         "data": "synthetic",
         "config": {"workload": w.name, "T": w.T, "N": w.N, "F": w.F, "P": w.P, "Q": w.Q, "B": w.B,
                    "storage": w.storage, "world": w.world, "rank": w.rank, "seed": w.seed,
                    "epochs": list(w.epochs), "batches_per_epoch": nb, "snapshots_timed": snaps,
-                   "batches_per_launch": k, "out_buffer_sets": sets, "order": args.order},
-        "gb_per_s": snaps * w.bytes_per_snapshot() / elapsed / 1e9,
-        "pct_of_hbm_peak": snaps * w.bytes_per_snapshot() / elapsed / 1e9 / HBM_PEAK_GBS * 100,
+                   "batches_per_launch": k, "out_buffer_sets": sets, "order": args.order,
+                   "out_dtype": args.out_dtype, "algorithmic_bytes_per_snapshot": bps},
+        "gb_per_s": snaps * bps / elapsed / 1e9,
+        "pct_of_hbm_peak": snaps * bps / elapsed / 1e9 / HBM_PEAK_GBS * 100,
         "roofline": {
             "bound": "hbm", "achieved": rate_k["achieved"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
             "frac": rate_k["achieved"] / HBM_PEAK_GBS, "traffic": traffic_from_profiles(w.name, k),
@@ -289,16 +296,16 @@ def main():
         "unique_bytes_ideal_per_launch": (
             rate_k["algorithmic_bytes_per_launch"] if args.order == "shuffle" else
             (rate_k["batches_per_launch"] * w.B + w.P + w.Q - 1) * w.N * w.F * (4 if w.storage == "f32" else 2)
-            + rate_k["batches_per_launch"] * w.B * (w.P + w.Q) * w.N * w.F * 4),
+            + rate_k["batches_per_launch"] * w.B * (w.P + w.Q) * w.N * w.F * out_elem),
         "one_batch_per_launch": {
             "value": snaps1 / elapsed1, "unit": "snapshots/s", "ms_per_step": elapsed1 / steps * 1e3,
-            "gb_per_s": snaps1 * w.bytes_per_snapshot() / elapsed1 / 1e9,
+            "gb_per_s": snaps1 * bps / elapsed1 / 1e9,
             "roofline": {"achieved": rate_1["achieved"], "frac": rate_1["achieved"] / HBM_PEAK_GBS,
                          **{kk: v for kk, v in rate_1.items() if kk != "achieved"}},
         },
         "epoch_indices_ms": t_idx * 1e3,
-        "copy_calibration": {"count": args.copy_calibration, "bytes_read": xs[0][0].numel() * 4,
-                             "bytes_written": xs[0][0].numel() * 4},
+        "copy_calibration": {"count": args.copy_calibration, "bytes_read": xs[0][0].numel() * xs[0][0].element_size(),
+                             "bytes_written": xs[0][0].numel() * xs[0][0].element_size()},
         "setup": {"generate_s": t_gen, "load_with_device_stats_s": t_load, "load_s": t_load2,
                   "load_with_alg1_train_stats_s": t_load_alg1,
                   "alg1_train_mean_std": [float(alg1_mean[0]), float(alg1_std[0])],

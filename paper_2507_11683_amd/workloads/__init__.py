@@ -50,11 +50,11 @@ class Workload:
     def series_bytes_f32(self) -> int:
         return self.T * self.N * self.F * 4
 
-    def bytes_per_snapshot(self) -> int:
+    def bytes_per_snapshot(self, out_bytes: int = 4) -> int:
         """Algorithmic bytes per snapshot: every element of the (P+Q)-step span is read once in
-        the storage type and written once as fp32."""
+        the storage type and written once in the output type (fp32 unless stated)."""
         s_in = 4 if self.storage == "f32" else 2
-        return (self.P + self.Q) * self.N * self.F * (s_in + 4)
+        return (self.P + self.Q) * self.N * self.F * (s_in + out_bytes)
 
 
 WORKLOADS = {
