@@ -265,6 +265,77 @@ __global__ void __launch_bounds__(THREADS) gather_rows_kernel(RowArgs a) {
     }
 }
 
+// bf16 storage AND bf16 outputs: a lane with one quad would move only 8 bytes each way and the
+// kernel becomes bound by the number of waves, not by memory.  Here a lane takes 8 consecutive
+// elements ("oct"): one 16-byte load, one 16-byte store.  Needs P*R and Q*R (span kernel) or R (row
+// kernel) to be multiples of 8.  The feature pattern of the second quad equals the first for
+// F in {1, 2, 4}; for other F it is looked up again.
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4_a2 __attribute__((ext_vector_type(4), aligned(2)));
+
+template <int FSTATIC, bool STREAM, bool FAST>
+__device__ __forceinline__ u32x4 standardised_oct(const void* series, int64_t e, uint32_t oct, const QuadStats& t,
+                                                  const GatherArgs& a) {
+    const u32x4_a2* p = reinterpret_cast<const u32x4_a2*>(static_cast<const uint16_t*>(series) + e);
+    const u32x4_a2 w = STREAM ? __builtin_nontemporal_load(p) : *p;
+    const f32x4 v0 = f32x4{widen_bf16_lo(w.x), widen_bf16_hi(w.x), widen_bf16_lo(w.y), widen_bf16_hi(w.y)};
+    const f32x4 v1 = f32x4{widen_bf16_lo(w.z), widen_bf16_hi(w.z), widen_bf16_lo(w.w), widen_bf16_hi(w.w)};
+    const f32x4 r0 = standardise_quad<FAST>(v0, t);
+    f32x4 r1;
+    if constexpr (FSTATIC != 0) r1 = standardise_quad<FAST>(v1, t);
+    else r1 = standardise_quad<FAST>(v1, quad_stats<0, FAST>(2 * oct + 1, a));
+    u32x4 o;
+    o.x = bf16_bits(r0.x) | (bf16_bits(r0.y) << 16);
+    o.y = bf16_bits(r0.z) | (bf16_bits(r0.w) << 16);
+    o.z = bf16_bits(r1.x) | (bf16_bits(r1.y) << 16);
+    o.w = bf16_bits(r1.z) | (bf16_bits(r1.w) << 16);
+    return o;
+}
+
+// Span kernel on octs: units_x / units_total count octs.
+template <int FSTATIC, int THREADS, bool STREAM, bool FAST>
+__global__ void __launch_bounds__(THREADS) gather_octs_kernel(GatherArgs a) {
+    const uint32_t j = blockIdx.y;
+    const uint32_t o = blockIdx.x * THREADS + threadIdx.x;
+    const int64_t e0 = span_offset(a, j);
+    const QuadStats t = quad_stats<FSTATIC, FAST>(2 * o, a);
+    pin_uniform<FSTATIC>(t);
+    if (o >= a.units_total) return;
+    const u32x4 r = standardised_oct<FSTATIC, STREAM, FAST>(a.series, e0 + 8ll * o, o, t, a);
+    u32x4* dst = (o < a.units_x)
+                     ? static_cast<u32x4*>(a.out_x) + static_cast<size_t>(j) * a.units_x + o
+                     : static_cast<u32x4*>(a.out_y) + static_cast<size_t>(j) * (a.units_total - a.units_x) +
+                           (o - a.units_x);
+    __builtin_nontemporal_store(r, dst);
+}
+
+// Row kernel on octs: row_quads counts octs per row.
+template <int FSTATIC, int THREADS, bool STREAM, bool FAST>
+__global__ void __launch_bounds__(THREADS) gather_rows_octs_kernel(RowArgs a) {
+    const uint32_t run = blockIdx.z, rr = blockIdx.y;
+    const uint32_t o = blockIdx.x * THREADS + threadIdx.x;
+    const uint32_t first_sample = run * a.B;
+    const uint32_t run_len = min(a.B, a.count - first_sample);
+    int32_t s0 = a.g.starts[first_sample];
+    const int32_t s0_max = a.g.last_start - static_cast<int32_t>(run_len - 1);
+    s0 = s0 < 0 ? 0 : (s0 > s0_max ? s0_max : s0);
+    const QuadStats t = quad_stats<FSTATIC, FAST>(2 * o, a.g);
+    pin_uniform<FSTATIC>(t);
+    if (rr >= run_len + a.PQ - 1 || o >= a.row_quads) return;
+    const int64_t e = (static_cast<int64_t>(s0) + rr) * a.g.R + 8ll * o;
+    const u32x4 r = standardised_oct<FSTATIC, STREAM, FAST>(a.g.series, e, o, t, a.g);
+    const uint32_t j_lo = (rr >= a.PQ - 1) ? rr - (a.PQ - 1) : 0u;
+    const uint32_t j_hi = (rr < run_len - 1) ? rr : run_len - 1;
+    const uint32_t Q = a.PQ - a.P;
+    for (uint32_t j = j_lo; j <= j_hi; ++j) {
+        const uint32_t p = rr - j;
+        const size_t sample = first_sample + j;
+        u32x4* dst = (p < a.P) ? static_cast<u32x4*>(a.g.out_x) + (sample * a.P + p) * a.row_quads + o
+                               : static_cast<u32x4*>(a.g.out_y) + (sample * Q + (p - a.P)) * a.row_quads + o;
+        __builtin_nontemporal_store(r, dst);
+    }
+}
+
 // Any geometry (P*R or Q*R not a multiple of 4): one element per thread.
 template <int STORE_BYTES, bool OUT_BF16>
 __global__ void __launch_bounds__(kThreads) gather_scalar_kernel(GatherArgs a) {
@@ -336,6 +407,31 @@ void launch_rows(const RowArgs& a, Switches sw, hipStream_t s) {
     });
 }
 
+template <int FSTATIC>
+void launch_octs(const GatherArgs& a, int32_t count, Switches sw, hipStream_t s) {
+    constexpr int kT = 256;
+    dim3 grid((a.units_total + kT - 1) / kT, count), block(kT);
+    with_bool(sw.stream_loads, [&](auto st) {
+        with_bool(sw.fast_divide, [&](auto fa) {
+            hipLaunchKernelGGL((gather_octs_kernel<FSTATIC, kT, decltype(st)::value, decltype(fa)::value>), grid, block,
+                               0, s, a);
+        });
+    });
+}
+
+template <int FSTATIC>
+void launch_rows_octs(const RowArgs& a, Switches sw, hipStream_t s) {
+    constexpr int kT = 256;
+    const uint32_t runs = (a.count + a.B - 1) / a.B;
+    dim3 grid((a.row_quads + kT - 1) / kT, a.B + a.PQ - 1, runs), block(kT);
+    with_bool(sw.stream_loads, [&](auto st) {
+        with_bool(sw.fast_divide, [&](auto fa) {
+            hipLaunchKernelGGL((gather_rows_octs_kernel<FSTATIC, kT, decltype(st)::value, decltype(fa)::value>), grid,
+                               block, 0, s, a);
+        });
+    });
+}
+
 // Picks the feature pattern: 1, 2 and 4 features are compile-time patterns, anything else generic.
 template <int STORE_BYTES, typename Fn>
 void with_feature_pattern(uint32_t F, Fn&& fn) {
@@ -360,14 +456,25 @@ void launch_for_storage(const pgti_ctx* c, GatherArgs& a, int32_t count, bool ou
         ra.PQ = static_cast<uint32_t>(c->P + c->Q);
         ra.row_quads = static_cast<uint32_t>(c->R / 4);
         const Switches sw{big_series, c->fast_divide, out_bf16};
-        with_feature_pattern<STORE_BYTES>(a.F, [&](auto fs) { launch_rows<STORE_BYTES, decltype(fs)::value>(ra, sw, s); });
+        if (STORE_BYTES == 2 && out_bf16 && c->R % 8 == 0) {
+            ra.row_quads = static_cast<uint32_t>(c->R / 8);  // octs per row
+            with_feature_pattern<STORE_BYTES>(a.F, [&](auto fs) { launch_rows_octs<decltype(fs)::value>(ra, sw, s); });
+        } else {
+            with_feature_pattern<STORE_BYTES>(a.F, [&](auto fs) { launch_rows<STORE_BYTES, decltype(fs)::value>(ra, sw, s); });
+        }
     } else if (c->path == GatherPath::kQuads) {
         a.units_x = static_cast<uint32_t>(ex / 4);
         a.units_total = static_cast<uint32_t>(et / 4);
         // Non-temporal loads once the series cannot live in the 256 MB last-level cache anyway
         // (with consecutive starts the rows are re-read by neighbouring samples: keep them cached).
         const Switches sw{big_series && !c->share_consecutive, c->fast_divide, out_bf16};
-        with_feature_pattern<STORE_BYTES>(a.F, [&](auto fs) { launch_quads<STORE_BYTES, decltype(fs)::value>(a, count, sw, s); });
+        if (STORE_BYTES == 2 && out_bf16 && ex % 8 == 0 && et % 8 == 0) {
+            a.units_x = static_cast<uint32_t>(ex / 8);  // octs
+            a.units_total = static_cast<uint32_t>(et / 8);
+            with_feature_pattern<STORE_BYTES>(a.F, [&](auto fs) { launch_octs<decltype(fs)::value>(a, count, sw, s); });
+        } else {
+            with_feature_pattern<STORE_BYTES>(a.F, [&](auto fs) { launch_quads<STORE_BYTES, decltype(fs)::value>(a, count, sw, s); });
+        }
     } else {
         a.units_x = static_cast<uint32_t>(ex);
         a.units_total = static_cast<uint32_t>(et);

@@ -564,24 +564,27 @@ def test_bf16_outputs(geom, storage_name, order_name):
             assert np.all(gx[total:] == canary) and np.all(gy[total:] == canary)
 
 
-def test_bf16_outputs_statewide_sampled(statewide_series):
+@pytest.mark.parametrize("storage_name", ["f32", "bf16"])
+def test_bf16_outputs_statewide_sampled(statewide_series, storage_name):
     w = workloads.WORKLOADS["statewide"]
     mean, std = _sampled_stats(statewide_series)
+    storage = pgti.PGTI_F32 if storage_name == "f32" else pgti.PGTI_BF16
+    ser_o = _oracle_series(statewide_series, storage)
     k = 4
     with pgti.Context(0) as ctx:
-        ctx.load_series(statewide_series, w.P, w.Q, w.B, pgti.PGTI_F32, mean, std)
-        ctx.epoch_indices(w.seed, 0)
-        share = ctx.get_indices()
+        ctx.load_series(statewide_series, w.P, w.Q, w.B, storage, mean, std)
         x = torch.empty((k, w.B, w.P, w.N, w.F), dtype=torch.bfloat16, device="cuda")
         y = torch.empty((k, w.B, w.Q, w.N, w.F), dtype=torch.bfloat16, device="cuda")
-        for first in (0, 2000):
+        for order_name, first in (("shuffle", 0), ("shuffle", 2000), ("sequential", 1500)):
+            ctx.epoch_indices_ex(ORDERS[order_name], seed=w.seed, epoch=0)
+            share = ctx.get_indices()
             total = ctx.build_batches_bf16(first, k, x, y)
             torch.cuda.synchronize()
             starts = share[first * w.B:(first + k) * w.B]
-            wx, wy = oracle.build_batch_bf16_out(statewide_series, oracle.F32, w.P, w.Q, mean, std, starts)
+            wx, wy = oracle.build_batch_bf16_out(ser_o, storage, w.P, w.Q, mean, std, starts)
             gx = x.view(torch.int16).cpu().numpy().view(np.uint16).reshape(k * w.B, w.P, w.N, w.F)[:total]
             gy = y.view(torch.int16).cpu().numpy().view(np.uint16).reshape(k * w.B, w.Q, w.N, w.F)[:total]
-            assert np.array_equal(gx, wx) and np.array_equal(gy, wy), first
+            assert np.array_equal(gx, wx) and np.array_equal(gy, wy), (order_name, first)
 
 
 def _ulp_close(a, b, ulps=1):
