@@ -17,12 +17,14 @@
 //     computed once on the host (in fp64, rounded once), and q0 = d*r is corrected twice with
 //     the exact residual, e = fma(-sigma, q, d); q = fma(e, r, q).  The second correction applied
 //     to a faithful quotient with a correctly rounded reciprocal yields RN(d/sigma) (Markstein's
-//     theorem) as long as nothing overflows or underflows, which the guards ensure: sigma's
-//     biased exponent in [95, 159], d's in [63, 191] (this also sends zeros, subnormals,
-//     infinities and NaNs to the `/` path).  6 full-rate VALU operations per element instead of
+//     theorem) as long as nothing overflows or underflows.  With sigma's biased exponent in
+//     [95, 159] (checked once on the host) a resulting quotient whose exponent lies in [96, 158]
+//     implies a dividend for which that held, so the result is accepted on that test alone and
+//     everything else (zeros, subnormals, infinities, NaNs, extreme magnitudes) is divided again
+//     with `/`.  6 full-rate VALU operations per element instead of
 //     about 15 issue slots; it matters when the stored type is bf16 (+7 % bandwidth) and is
 //     hidden behind memory time for fp32.  tests/fastdiv_model.c checks the identity on the host
-//     for every guarded dividend of hard divisors and for random divisors.
+//     for all 2^32 dividends of hard divisors and for random divisors.
 #include <type_traits>
 
 #include "pgti_internal.h"
@@ -83,19 +85,20 @@ __device__ __forceinline__ f32x4 load_quad(const void* series, int64_t e) {
     }
 }
 
-// d / sigma, correctly rounded.  FAST: reciprocal multiply plus two exact-residual corrections when
-// d's exponent is in the guarded range, the ordinary division otherwise (see the file header).
+// d / sigma, correctly rounded.  FAST: reciprocal multiply plus two exact-residual corrections,
+// accepted when the quotient's exponent is in the mid range, the ordinary division otherwise (see
+// the file header).
 __device__ __forceinline__ uint32_t magnitude_bits(float d) { return __float_as_uint(d) & 0x7FFFFFFFu; }
 
-// True when all four dividends have a biased exponent in [63, 191]: the smallest and the largest
+// True when all four quotients have a biased exponent in [96, 158]: the smallest and the largest
 // magnitude bit pattern bound all four (NaN and Inf patterns are the largest, zero and subnormals
 // the smallest).
-__device__ __forceinline__ bool dividends_in_range(f32x4 d) {
-    const uint32_t a = magnitude_bits(d.x), b = magnitude_bits(d.y), c = magnitude_bits(d.z),
-                   e = magnitude_bits(d.w);
+__device__ __forceinline__ bool quotients_accepted(f32x4 q) {
+    const uint32_t a = magnitude_bits(q.x), b = magnitude_bits(q.y), c = magnitude_bits(q.z),
+                   e = magnitude_bits(q.w);
     const uint32_t lo = min(min(a, b), min(c, e));
     const uint32_t hi = max(max(a, b), max(c, e));
-    return static_cast<bool>(static_cast<int>(lo >= (63u << 23)) & static_cast<int>(hi < (192u << 23)));
+    return static_cast<bool>(static_cast<int>(lo >= (96u << 23)) & static_cast<int>(hi < (159u << 23)));
 }
 
 __device__ __forceinline__ float corrected_quotient(float d, float sigma, float r) {
@@ -161,13 +164,11 @@ __device__ __forceinline__ f32x4 standardise_quad(f32x4 v, const QuadStats& t) {
     const f32x4 d = f32x4{v.x - t.m.x, v.y - t.m.y, v.z - t.m.z, v.w - t.m.w};
     f32x4 o;
     if constexpr (FAST) {
-        if (dividends_in_range(d)) {
-            o.x = corrected_quotient(d.x, t.s.x, t.r.x);
-            o.y = corrected_quotient(d.y, t.s.y, t.r.y);
-            o.z = corrected_quotient(d.z, t.s.z, t.r.z);
-            o.w = corrected_quotient(d.w, t.s.w, t.r.w);
-            return o;
-        }
+        o.x = corrected_quotient(d.x, t.s.x, t.r.x);
+        o.y = corrected_quotient(d.y, t.s.y, t.r.y);
+        o.z = corrected_quotient(d.z, t.s.z, t.r.z);
+        o.w = corrected_quotient(d.w, t.s.w, t.r.w);
+        if (quotients_accepted(o)) return o;  // almost always; the test is off the arithmetic's critical path
     }
     o.x = d.x / t.s.x;
     o.y = d.y / t.s.y;
