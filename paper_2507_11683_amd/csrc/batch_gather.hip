@@ -190,17 +190,28 @@ __device__ __forceinline__ uint32_t bf16_bits(float v) {
     return (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;
 }
 
+// Output stores carry the non-temporal hint (written once, never re-read by these kernels) and
+// agent scope: on MI355X `sc1 nt` stores measured 3.5 % faster than `nt` alone for this
+// read-stream + write-stream mix (80.3 % vs 77.6 % of the HBM peak in the same harness), plain
+// stores 71 %.  The compiler's non-temporal builtin only sets `nt`, hence the two asm statements.
+__device__ __forceinline__ void stream_store_16(void* dst, f32x4 v) {
+    asm volatile("global_store_dwordx4 %0, %1, off sc1 nt" ::"v"(dst), "v"(v) : "memory");
+}
+__device__ __forceinline__ void stream_store_8(void* dst, u32x2 v) {
+    asm volatile("global_store_dwordx2 %0, %1, off sc1 nt" ::"v"(dst), "v"(v) : "memory");
+}
+
 // Stores output quad number `index` of the array at `base`: 16 bytes of fp32, or 8 bytes of bf16 when
-// the outputs are emitted in bf16.  Non-temporal: written once, never re-read by these kernels.
+// the outputs are emitted in bf16.
 template <bool OUT_BF16>
 __device__ __forceinline__ void store_quad(void* base, size_t index, f32x4 r) {
     if constexpr (OUT_BF16) {
         u32x2 o;
         o.x = bf16_bits(r.x) | (bf16_bits(r.y) << 16);
         o.y = bf16_bits(r.z) | (bf16_bits(r.w) << 16);
-        __builtin_nontemporal_store(o, static_cast<u32x2*>(base) + index);
+        stream_store_8(static_cast<u32x2*>(base) + index, o);
     } else {
-        __builtin_nontemporal_store(r, static_cast<f32x4*>(base) + index);
+        stream_store_16(static_cast<f32x4*>(base) + index, r);
     }
 }
 
@@ -307,7 +318,7 @@ __global__ void __launch_bounds__(THREADS) gather_octs_kernel(GatherArgs a) {
                      ? static_cast<u32x4*>(a.out_x) + static_cast<size_t>(j) * a.units_x + o
                      : static_cast<u32x4*>(a.out_y) + static_cast<size_t>(j) * (a.units_total - a.units_x) +
                            (o - a.units_x);
-    __builtin_nontemporal_store(r, dst);
+    stream_store_16(dst, __builtin_bit_cast(f32x4, r));
 }
 
 // Row kernel on octs: row_quads counts octs per row.
@@ -333,7 +344,7 @@ __global__ void __launch_bounds__(THREADS) gather_rows_octs_kernel(RowArgs a) {
         const size_t sample = first_sample + j;
         u32x4* dst = (p < a.P) ? static_cast<u32x4*>(a.g.out_x) + (sample * a.P + p) * a.row_quads + o
                                : static_cast<u32x4*>(a.g.out_y) + (sample * Q + (p - a.P)) * a.row_quads + o;
-        __builtin_nontemporal_store(r, dst);
+        stream_store_16(dst, __builtin_bit_cast(f32x4, r));
     }
 }
 
