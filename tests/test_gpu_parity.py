@@ -479,6 +479,40 @@ def test_multi_batch_launch_matches_oracle_and_single_launches(storage_name):
             assert rc == pgti.PGTI_ERR_RANGE, (first, k, rc)
 
 
+@pytest.mark.parametrize("order_name", ["shuffle", "sequential"])
+@pytest.mark.parametrize("out_dtype", ["f32", "bf16"])
+def test_more_samples_than_one_grid_holds(order_name, out_dtype):
+    # 1,100 batches of 64 = 70,400 samples in one call: more than the 65,535 a grid dimension holds,
+    # so the call is split into launches of whole batches
+    T, N, F, P, Q, B = 70500, 1, 4, 3, 2, 64
+    rng = np.random.default_rng(77)
+    series = rng.normal(10, 3, (T, N, F)).astype(np.float32)
+    mean, std = np.array([10, 9, 11, 0], np.float32), np.array([3, 2.5, 3.5, 1], np.float32)
+    k = 1100
+    with pgti.Context(0) as ctx:
+        ctx.load_series(series, P, Q, B, pgti.PGTI_F32, mean, std)
+        ctx.epoch_indices_ex(ORDERS[order_name], seed=3, epoch=0)
+        share = ctx.get_indices()
+        assert ctx.num_batches() >= k + 1
+        starts = share[B:(k + 1) * B]
+        if out_dtype == "f32":
+            x = torch.empty((k, B, P, N, F), dtype=torch.float32, device="cuda")
+            y = torch.empty((k, B, Q, N, F), dtype=torch.float32, device="cuda")
+            assert ctx.build_batches(1, k, x, y) == k * B
+            torch.cuda.synchronize()
+            wx, wy = oracle.build_batch(series, oracle.F32, P, Q, mean, std, starts)
+            assert np.array_equal(x.cpu().numpy().reshape(wx.shape).view(np.uint32), wx.view(np.uint32))
+            assert np.array_equal(y.cpu().numpy().reshape(wy.shape).view(np.uint32), wy.view(np.uint32))
+        else:
+            x = torch.empty((k, B, P, N, F), dtype=torch.bfloat16, device="cuda")
+            y = torch.empty((k, B, Q, N, F), dtype=torch.bfloat16, device="cuda")
+            assert ctx.build_batches_bf16(1, k, x, y) == k * B
+            torch.cuda.synchronize()
+            wx, wy = oracle.build_batch_bf16_out(series, oracle.F32, P, Q, mean, std, starts)
+            assert np.array_equal(x.view(torch.int16).cpu().numpy().view(np.uint16).reshape(wx.shape), wx)
+            assert np.array_equal(y.view(torch.int16).cpu().numpy().view(np.uint16).reshape(wy.shape), wy)
+
+
 def test_multi_batch_statewide_sampled(statewide_series):
     # the launch shape the benchmark times: 4 batches of 32 per launch at full size
     w = workloads.WORKLOADS["statewide"]
