@@ -50,7 +50,8 @@ typedef enum {
 int pgti_create(pgti_ctx** out, int device);
 
 /* Frees everything the context owns after waiting for the device work it enqueued on its own
- * stream.  The caller must have finished (or synchronised) its own streams first.  NULL is ok. */
+ * stream and for the streams that received batch builds since the last epoch-index generation.
+ * Streams must still exist at this point.  NULL is ok. */
 void pgti_destroy(pgti_ctx* c);
 
 /*
@@ -64,8 +65,8 @@ void pgti_destroy(pgti_ctx* c);
  * (Algorithm 1 standardises with (v - mu) / sigma).  If BOTH are NULL the library computes, on
  * the device, the mean and the population standard deviation of every feature over all T*N
  * values of the fp32 input.  Exactly one of them NULL is PGTI_ERR_ARG.
- * Replaces any series loaded before; invalidates epoch indices.  Synchronous: on return the
- * host buffers are no longer referenced.
+ * Replaces any series loaded before (after waiting for batch builds still in flight on it);
+ * invalidates epoch indices.  Synchronous: on return the host buffers are no longer referenced.
  * Errors: ARG, RANGE (T < P + Q, or n >= 2^31), STATS, OOM, HIP.
  */
 int pgti_load_series(pgti_ctx* c, const float* host_series, int64_t T, int32_t N, int32_t F,

@@ -148,6 +148,8 @@ int load_impl(pgti_ctx* c, const float* src, const pgti_load_spec* spec) {
     if (guard.status != hipSuccess) return fail_hip(guard.status, "hipSetDevice");
     hipStream_t ws = c->work_stream;
     PGTI_HIP_TRY(hipStreamSynchronize(ws));
+    // Batch builds enqueued through this context may still read the series that is about to go.
+    for (int k = 0; k < c->n_tracked; ++k) PGTI_HIP_TRY(hipStreamSynchronize(c->tracked[k].stream));
     free_series(c);
     c->n_tracked = 0;
 
@@ -384,6 +386,7 @@ void pgti_destroy(pgti_ctx* c) {
     if (!c) return;
     DeviceGuard guard(c->device);
     if (c->work_stream) (void)hipStreamSynchronize(c->work_stream);
+    for (int k = 0; k < c->n_tracked; ++k) (void)hipStreamSynchronize(c->tracked[k].stream);
     free_series(c);
     for (int k = 0; k < kMaxTrackedStreams; ++k)
         if (c->tracked[k].event) (void)hipEventDestroy(c->tracked[k].event);
