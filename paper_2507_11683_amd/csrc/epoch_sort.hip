@@ -7,6 +7,10 @@
 // over 8-bit digits of the 64-bit key, the start index riding along as the value.  Stability of
 // every pass makes the index the tiebreak.
 //
+// With at most 256 tiles (n <= 524,288 keys, every benchmark workload) a pass is ONE launch: the
+// count table is tile-major, each scatter workgroup sums the columns of the tiles before it by
+// itself (a coalesced walk over at most 256 rows), counts the next pass's digits into a second
+// table and clears its row of a third one for the pass after that.  Larger n:
 // One pass = two launches:
 //   scan    : exclusive prefix over workgroups of the per-(digit, workgroup) counts, digit totals
 //   scatter : each workgroup ranks its tile (wave ballots give every key its rank among equal
@@ -30,6 +34,7 @@ constexpr uint32_t kWave = 64;
 constexpr uint32_t kWaves = kThreads / kWave;
 constexpr uint32_t kItems = kSortTile / kThreads;  // rounds per wave: 8
 constexpr uint32_t kRadix = 256;
+constexpr uint32_t kFusedScanTiles = 256;  // up to this many tiles a scatter workgroup scans the counts itself
 constexpr uint64_t kGamma = 0x9E3779B97F4A7C15ull;
 static_assert(kRadix == kThreads, "one thread per digit in the scan steps");
 static_assert(kItems * kThreads == kSortTile, "tile must be a whole number of rounds");
@@ -59,10 +64,12 @@ __device__ __forceinline__ uint32_t block_inclusive_scan(uint32_t v, uint32_t* l
 
 // keys[i] = key(seed, epoch, counter_base + i*counter_stride) for i < n; counts of the lowest digit
 // per (digit, workgroup) into hist0[digit][wg].
+// TILE_MAJOR: counts go to hist0[wg][digit] and this workgroup's row of hist1 is cleared.
+template <bool TILE_MAJOR>
 __global__ void __launch_bounds__(kThreads) keygen_kernel(uint64_t seed, uint64_t epoch, uint32_t n,
                                                           uint32_t nblk, uint64_t counter_base,
                                                           uint64_t counter_stride, uint64_t* keys,
-                                                          uint32_t* hist0) {
+                                                          uint32_t* hist0, uint32_t* hist1) {
     __shared__ uint32_t counts[kRadix];
     const uint32_t tid = threadIdx.x, b = blockIdx.x;
     counts[tid] = 0;
@@ -79,7 +86,12 @@ __global__ void __launch_bounds__(kThreads) keygen_kernel(uint64_t seed, uint64_
         }
     }
     __syncthreads();
-    hist0[tid * nblk + b] = counts[tid];
+    if constexpr (TILE_MAJOR) {
+        hist0[b * kRadix + tid] = counts[tid];
+        hist1[b * kRadix + tid] = 0u;
+    } else {
+        hist0[tid * nblk + b] = counts[tid];
+    }
 }
 
 // One workgroup per digit d: hist[d][0..nblk) becomes its exclusive prefix, tot[d] its sum.
@@ -112,13 +124,16 @@ __global__ void __launch_bounds__(kThreads) scan_kernel(uint32_t* hist, uint32_t
 // FIRST: values are the element positions themselves (no value array yet).
 // LAST : only the values whose destination falls in [lo, hi) are written, to share[pos - lo],
 //        with value_offset added (the first start of the range the positions refer to).
-template <bool FIRST, bool LAST>
+// FUSED: `hist_scanned` holds RAW tile-major counts [tile][digit]; the prefix over earlier tiles and
+//        the digit totals are summed here, `hist_next` is tile-major too and `hist_clear` (the
+//        table of the pass after next) gets this workgroup's row zeroed.  `tot` is unused.
+template <bool FIRST, bool LAST, bool FUSED>
 __global__ void __launch_bounds__(kThreads) scatter_kernel(
     const uint64_t* __restrict__ keys_in, const int32_t* __restrict__ vals_in,
     uint64_t* __restrict__ keys_out, int32_t* __restrict__ vals_out,
     const uint32_t* __restrict__ hist_scanned, const uint32_t* __restrict__ tot,
-    uint32_t* __restrict__ hist_next, uint32_t n, uint32_t nblk, uint32_t shift,
-    int32_t* __restrict__ share, uint32_t lo, uint32_t hi, int32_t value_offset) {
+    uint32_t* __restrict__ hist_next, uint32_t* __restrict__ hist_clear, uint32_t n, uint32_t nblk,
+    uint32_t shift, int32_t* __restrict__ share, uint32_t lo, uint32_t hi, int32_t value_offset) {
     __shared__ uint32_t wave_counts[kWaves][kRadix];  // running counts, later wave-exclusive offsets
     __shared__ uint32_t digit_base[kRadix];
     __shared__ uint32_t scan_tmp[kThreads];
@@ -176,9 +191,30 @@ __global__ void __launch_bounds__(kThreads) scatter_kernel(
             wave_counts[k][tid] = run;
             run += cnt;
         }
-        const uint32_t t = tot[tid];
+        uint32_t t, before;
+        if constexpr (FUSED) {
+            t = 0;
+            before = 0;
+            // Coalesced: 256 consecutive counts per tile.  16 independent loads are issued before
+            // the first is used, otherwise the walk costs one L2 latency per tile.
+            for (uint32_t base = 0; base < nblk; base += 16) {
+                uint32_t cnt[16];
+#pragma unroll
+                for (uint32_t u = 0; u < 16; ++u)
+                    cnt[u] = (base + u < nblk) ? hist_scanned[(base + u) * kRadix + tid] : 0u;
+#pragma unroll
+                for (uint32_t u = 0; u < 16; ++u) {
+                    t += cnt[u];
+                    before += (base + u < b) ? cnt[u] : 0u;
+                }
+            }
+            hist_clear[b * kRadix + tid] = 0u;
+        } else {
+            t = tot[tid];
+            before = hist_scanned[static_cast<size_t>(tid) * nblk + b];
+        }
         const uint32_t incl = block_inclusive_scan(t, scan_tmp);
-        digit_base[tid] = (incl - t) + hist_scanned[static_cast<size_t>(tid) * nblk + b];
+        digit_base[tid] = (incl - t) + before;
     }
     __syncthreads();
 
@@ -193,7 +229,8 @@ __global__ void __launch_bounds__(kThreads) scatter_kernel(
             keys_out[pos] = key[r];
             vals_out[pos] = val[r];
             const uint32_t dn = static_cast<uint32_t>(key[r] >> (shift + 8)) & 0xFFu;
-            atomicAdd(&hist_next[static_cast<size_t>(dn) * nblk + pos / kSortTile], 1u);
+            if constexpr (FUSED) atomicAdd(&hist_next[(pos / kSortTile) * kRadix + dn], 1u);
+            else atomicAdd(&hist_next[static_cast<size_t>(dn) * nblk + pos / kSortTile], 1u);
         } else {
             if (pos >= lo && pos < hi) share[pos - lo] = val[r] + value_offset;
         }
@@ -220,32 +257,52 @@ __global__ void __launch_bounds__(kThreads) expand_batches_kernel(const int32_t*
 
 }  // namespace
 
+namespace {
+
+template <bool FUSED>
+void launch_pass(pgti_ctx* c, uint32_t pass, uint32_t n, uint32_t nblk, const SortPlan& plan, uint32_t* hist,
+                 uint32_t* hist_next, uint32_t* hist_clear, hipStream_t s) {
+    const uint64_t* kin = c->d_keys[pass & 1];
+    const int32_t* vin = c->d_vals[pass & 1];
+    uint64_t* kout = c->d_keys[(pass + 1) & 1];
+    int32_t* vout = c->d_vals[(pass + 1) & 1];
+    const dim3 grid(nblk), block(kThreads);
+    if (pass == 0)
+        hipLaunchKernelGGL((scatter_kernel<true, false, FUSED>), grid, block, 0, s, kin, vin, kout, vout, hist, c->d_tot,
+                           hist_next, hist_clear, n, nblk, 8 * pass, plan.out, plan.out_lo, plan.out_hi,
+                           plan.value_offset);
+    else if (pass < 7)
+        hipLaunchKernelGGL((scatter_kernel<false, false, FUSED>), grid, block, 0, s, kin, vin, kout, vout, hist, c->d_tot,
+                           hist_next, hist_clear, n, nblk, 8 * pass, plan.out, plan.out_lo, plan.out_hi,
+                           plan.value_offset);
+    else
+        hipLaunchKernelGGL((scatter_kernel<false, true, FUSED>), grid, block, 0, s, kin, vin, kout, vout, hist, c->d_tot,
+                           hist_next, hist_clear, n, nblk, 8 * pass, plan.out, plan.out_lo, plan.out_hi,
+                           plan.value_offset);
+}
+
+}  // namespace
+
 hipError_t launch_sorted_order(pgti_ctx* c, uint64_t seed, uint64_t epoch, const SortPlan& plan, hipStream_t s) {
     const uint32_t n = plan.n_keys;
     if (n == 0) return hipSuccess;
     const uint32_t nblk = (n + kSortTile - 1) / kSortTile;
-    hipLaunchKernelGGL(keygen_kernel, dim3(nblk), dim3(kThreads), 0, s, seed, epoch, n, nblk, plan.counter_base,
-                       plan.counter_stride, c->d_keys[0], c->d_hist[0]);
-    for (uint32_t pass = 0; pass < 8; ++pass) {
-        uint32_t* hist = c->d_hist[pass & 1];
-        uint32_t* hist_next = c->d_hist[(pass + 1) & 1];
-        const uint64_t* kin = c->d_keys[pass & 1];
-        const int32_t* vin = c->d_vals[pass & 1];
-        uint64_t* kout = c->d_keys[(pass + 1) & 1];
-        int32_t* vout = c->d_vals[(pass + 1) & 1];
-        hipLaunchKernelGGL(scan_kernel, dim3(kRadix), dim3(kThreads), 0, s, hist, c->d_tot, hist_next, nblk);
-        if (pass == 0)
-            hipLaunchKernelGGL((scatter_kernel<true, false>), dim3(nblk), dim3(kThreads), 0, s, kin, vin, kout, vout,
-                               hist, c->d_tot, hist_next, n, nblk, 8 * pass, plan.out, plan.out_lo, plan.out_hi,
-                               plan.value_offset);
-        else if (pass < 7)
-            hipLaunchKernelGGL((scatter_kernel<false, false>), dim3(nblk), dim3(kThreads), 0, s, kin, vin, kout, vout,
-                               hist, c->d_tot, hist_next, n, nblk, 8 * pass, plan.out, plan.out_lo, plan.out_hi,
-                               plan.value_offset);
-        else
-            hipLaunchKernelGGL((scatter_kernel<false, true>), dim3(nblk), dim3(kThreads), 0, s, kin, vin, kout, vout,
-                               hist, c->d_tot, hist_next, n, nblk, 8 * pass, plan.out, plan.out_lo, plan.out_hi,
-                               plan.value_offset);
+    if (nblk <= kFusedScanTiles) {
+        // 1 + 8 launches; three count tables rotate: read / count the next pass / cleared for the one after.
+        hipLaunchKernelGGL(keygen_kernel<true>, dim3(nblk), dim3(kThreads), 0, s, seed, epoch, n, nblk,
+                           plan.counter_base, plan.counter_stride, c->d_keys[0], c->d_hist[0], c->d_hist[1]);
+        for (uint32_t pass = 0; pass < 8; ++pass)
+            launch_pass<true>(c, pass, n, nblk, plan, c->d_hist[pass % 3], c->d_hist[(pass + 1) % 3],
+                              c->d_hist[(pass + 2) % 3], s);
+    } else {
+        hipLaunchKernelGGL(keygen_kernel<false>, dim3(nblk), dim3(kThreads), 0, s, seed, epoch, n, nblk,
+                           plan.counter_base, plan.counter_stride, c->d_keys[0], c->d_hist[0], c->d_hist[1]);
+        for (uint32_t pass = 0; pass < 8; ++pass) {
+            uint32_t* hist = c->d_hist[pass & 1];
+            uint32_t* hist_next = c->d_hist[(pass + 1) & 1];
+            hipLaunchKernelGGL(scan_kernel, dim3(kRadix), dim3(kThreads), 0, s, hist, c->d_tot, hist_next, nblk);
+            launch_pass<false>(c, pass, n, nblk, plan, hist, hist_next, nullptr, s);
+        }
     }
     return hipGetLastError();
 }

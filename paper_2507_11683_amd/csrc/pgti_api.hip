@@ -45,6 +45,7 @@ void free_series(pgti_ctx* c) {
     drop(c->d_vals[1]);
     drop(c->d_hist[0]);
     drop(c->d_hist[1]);
+    drop(c->d_hist[2]);
     drop(c->d_tot);
     drop(c->d_share);
     c->loaded = false;
@@ -180,6 +181,7 @@ int load_impl(pgti_ctx* c, const float* src, const pgti_load_spec* spec) {
     if (int rc = alloc(&c->d_vals[1], sizeof(int32_t) * n)) return rc;
     if (int rc = alloc(&c->d_hist[0], sizeof(uint32_t) * 256 * nblk)) return rc;
     if (int rc = alloc(&c->d_hist[1], sizeof(uint32_t) * 256 * nblk)) return rc;
+    if (int rc = alloc(&c->d_hist[2], sizeof(uint32_t) * 256 * nblk)) return rc;
     if (int rc = alloc(&c->d_tot, sizeof(uint32_t) * 256)) return rc;
     if (int rc = alloc(&c->d_share, sizeof(int32_t) * n)) return rc;
     c->series_bytes = elems * store_bytes;

@@ -54,7 +54,7 @@ struct pgti_ctx {
     hipStream_t work_stream = nullptr;  // owns the sort and the load-time kernels
     uint64_t* d_keys[2] = {nullptr, nullptr};
     int32_t* d_vals[2] = {nullptr, nullptr};
-    uint32_t* d_hist[2] = {nullptr, nullptr};  // [256][nblk] digit-major block counts, ping-pong
+    uint32_t* d_hist[3] = {nullptr, nullptr, nullptr};  // per-(digit, tile) counts, rotating tables
     uint32_t* d_tot = nullptr;                 // [256] digit totals of the current pass
     int32_t* d_share = nullptr;                // this rank's starts, capacity n_windows
     uint32_t sort_blocks = 0;
