@@ -116,7 +116,7 @@ def main():
     args = parse_args()
     if args.gpus != 1:
         print(f"bench.py: this build runs on one GPU; --gpus {args.gpus} is not supported (every rank would "
-              "hold the full series and build its own contiguous share of the same shuffle; see DESIGN.md)",
+              "hold the full series and build its own contiguous share of the same shuffle, with no exchange step)",
               file=sys.stderr)
         sys.exit(2)
 
