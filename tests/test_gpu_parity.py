@@ -438,6 +438,32 @@ def test_batches_follow_new_epoch_without_host_sync():
             assert _bits_equal(y[:len(last)].cpu().numpy(), wy)
 
 
+def test_more_streams_than_tracked_slots():
+    # the context tracks 8 streams between two index generations; builds on 11 streams still order
+    # correctly against the next sort and give the right batches
+    w = workloads.WORKLOADS["tiny"]
+    series = workloads.make_series(w)
+    mean, std = oracle.series_stats(series)
+    streams = [torch.cuda.Stream() for _ in range(11)]
+    with pgti.Context(0) as ctx:
+        ctx.load_series(series, w.P, w.Q, w.B, pgti.PGTI_F32, mean, std)
+        for epoch in (0, 1):
+            ctx.epoch_indices(9, epoch)
+            outs = []
+            for b, st in enumerate(streams):
+                x, y = _alloc_out(w.B, w.P, w.Q, w.N, w.F)
+                ctx.build_batch(b, x, y, stream=st)
+                outs.append((b, x, y))
+            share = oracle.epoch_indices(9, epoch, 0, 1, w.n_windows)
+            if epoch == 0:
+                continue  # next sort is enqueued while these builds may still run
+            torch.cuda.synchronize()
+            for b, x, y in outs:
+                wx, wy = oracle.build_batch(series, oracle.F32, w.P, w.Q, mean, std, share[b * w.B:(b + 1) * w.B])
+                assert _bits_equal(x.cpu().numpy(), wx) and _bits_equal(y.cpu().numpy(), wy), b
+        torch.cuda.synchronize()
+
+
 # ----------------------------------------------------------------------------------------------
 # several batches per launch
 # ----------------------------------------------------------------------------------------------
