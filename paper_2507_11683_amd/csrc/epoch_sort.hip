@@ -20,6 +20,10 @@
 //             order independent), so no separate counting launch is needed.
 // The key generation launch also produces the counts of pass 0.
 //
+// Up to 4096 keys (small datasets, validation and test ranges, batch-level shuffles) the whole order
+// comes from ONE launch of one workgroup: keys are generated into LDS and ordered by (key, index)
+// with a bitonic network; (key, index) pairs are all distinct, so the result is the same order.
+//
 // Other orders reuse the same machinery: the sequential order (validation / test passes over a
 // range of starts, Sec. 3.1) is an iota; the batch-level shuffle of Sec. 5.4 (fixed partition,
 // batch order shuffled, batch contents fixed) sorts one key per full batch and expands the sorted
@@ -237,6 +241,48 @@ __global__ void __launch_bounds__(kThreads) scatter_kernel(
     }
 }
 
+// One workgroup orders up to kSmallSortKeys keys in LDS.  Slots n..m-1 (m = n rounded up to a power
+// of two) hold the largest key with their own slot number as index, which is above every real
+// index, so they end up behind the n real entries.
+constexpr uint32_t kSmallSortKeys = 4096;
+constexpr uint32_t kSmallSortThreads = 1024;
+
+__global__ void __launch_bounds__(kSmallSortThreads) small_sort_kernel(uint64_t seed, uint64_t epoch, uint32_t n,
+                                                                        uint32_t m, uint64_t counter_base,
+                                                                        uint64_t counter_stride,
+                                                                        int32_t* __restrict__ share, uint32_t lo,
+                                                                        uint32_t hi, int32_t value_offset) {
+    __shared__ uint64_t key[kSmallSortKeys];
+    __shared__ uint32_t idx[kSmallSortKeys];
+    const uint32_t tid = threadIdx.x;
+    const uint64_t h0 = mix64(seed + kGamma);
+    const uint64_t h1 = mix64((h0 ^ epoch) + kGamma);
+    for (uint32_t i = tid; i < m; i += kSmallSortThreads) {
+        key[i] = (i < n) ? mix64((h1 ^ (counter_base + i * counter_stride)) + kGamma) : ~0ull;
+        idx[i] = i;
+    }
+    __syncthreads();
+    for (uint32_t size = 2; size <= m; size <<= 1) {
+        for (uint32_t stride = size >> 1; stride > 0; stride >>= 1) {
+            for (uint32_t t = tid; t < (m >> 1); t += kSmallSortThreads) {
+                const uint32_t a = ((t & ~(stride - 1)) << 1) | (t & (stride - 1));
+                const uint32_t b = a + stride;
+                const uint64_t ka = key[a], kb = key[b];
+                const uint32_t ia = idx[a], ib = idx[b];
+                const bool a_after_b = (ka > kb) || (ka == kb && ia > ib);
+                const bool ascending = (a & size) == 0;
+                if (a_after_b == ascending) {
+                    key[a] = kb; key[b] = ka;
+                    idx[a] = ib; idx[b] = ia;
+                }
+            }
+            __syncthreads();
+        }
+    }
+    for (uint32_t i = tid; i < n; i += kSmallSortThreads)
+        if (i >= lo && i < hi) share[i - lo] = static_cast<int32_t>(idx[i]) + value_offset;
+}
+
 // share[i] = first + i (sequential order).
 __global__ void __launch_bounds__(kThreads) iota_kernel(int32_t* __restrict__ share, uint32_t len, int32_t first) {
     const uint32_t i = blockIdx.x * kThreads + threadIdx.x;
@@ -286,6 +332,14 @@ void launch_pass(pgti_ctx* c, uint32_t pass, uint32_t n, uint32_t nblk, const So
 hipError_t launch_sorted_order(pgti_ctx* c, uint64_t seed, uint64_t epoch, const SortPlan& plan, hipStream_t s) {
     const uint32_t n = plan.n_keys;
     if (n == 0) return hipSuccess;
+    if (n <= kSmallSortKeys) {
+        uint32_t m = 1;
+        while (m < n) m <<= 1;
+        hipLaunchKernelGGL(small_sort_kernel, dim3(1), dim3(kSmallSortThreads), 0, s, seed, epoch, n, m,
+                           plan.counter_base, plan.counter_stride, plan.out, plan.out_lo, plan.out_hi,
+                           plan.value_offset);
+        return hipGetLastError();
+    }
     const uint32_t nblk = (n + kSortTile - 1) / kSortTile;
     if (nblk <= kFusedScanTiles) {
         // 1 + 8 launches; three count tables rotate: read / count the next pass / cleared for the one after.

@@ -244,9 +244,10 @@ def test_identity_channel_returns_stored_bits():
 # ----------------------------------------------------------------------------------------------
 # index generation on its own
 # ----------------------------------------------------------------------------------------------
-@pytest.mark.parametrize("n", [1, 2, 63, 64, 65, 2047, 2048, 2049, 4096, 10000, 105097, 500000, 524288, 524289, 1300003])
+@pytest.mark.parametrize("n", [1, 2, 3, 63, 64, 65, 1977, 2047, 2048, 2049, 3000, 4095, 4096, 4097, 10000, 105097, 500000, 524288, 524289, 1300003])
 def test_epoch_order_sizes(n):
-    # n spans one lane, one wave, one tile, several tiles with a ragged tail, and more than 256 tiles
+    # n spans one lane, one wave, the single-workgroup path up to 4096 keys (powers of two and ragged
+    # sizes), several tiles with a ragged tail, and more than 256 tiles
     # (the per-digit scan over workgroups then runs in several chunks with a carry)
     P = Q = 1
     T = n + P + Q - 1
