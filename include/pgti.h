@@ -200,12 +200,14 @@ int64_t pgti_num_batches(pgti_ctx* c);
  *
  * Batch `batch_no` holds the samples share[batch_no*B ... min((batch_no+1)*B, n_share)) in that
  * order.  For sample j with start s:  out_x[j, p, :, f] = (S[s+p, :, f] - mean[f]) / std[f],
- * p < P;  out_y[j, q, :, f] = (S[s+P+q, :, f] - mean[f]) / std[f], q < Q.  The subtraction and
- * the division are two separately rounded IEEE binary32 operations (no FMA, no reciprocal);
- * bf16 storage is widened exactly first.
+ * p < P;  out_y[j, q, :, f] = (S[s+P+q, :, f] - mean[f]) / std[f], q < Q.  Every output has the
+ * bits of two separately rounded IEEE binary32 operations, a subtraction and a correctly rounded
+ * division (however the kernel arrives at that quotient); bf16 storage is widened exactly first.
  * out_x: DEVICE fp32 [B, P, N, F]; out_y: DEVICE fp32 [B, Q, N, F]; caller-owned, 16-byte
  * aligned.  `stream` is a hipStream_t passed as void* (NULL = the default stream).  The kernel
- * is enqueued and the call returns without synchronising.
+ * is enqueued and the call returns without synchronising.  The stream must stay alive until the
+ * next epoch-index generation, load or destroy call on this context has returned: those calls
+ * order themselves behind the builds enqueued on it.
  * Returns the number of valid samples B' in 1..B.  A short last batch is not padded: rows
  * j >= B' of the outputs are left untouched.
  * Errors: STATE, RANGE (batch_no outside [0, num_batches)), ARG (null or misaligned), HIP.
