@@ -563,6 +563,34 @@ def test_multi_batch_statewide_sampled(statewide_series):
             assert _bits_equal(gx, wx) and _bits_equal(gy, wy), first
 
 
+@pytest.mark.parametrize("order_name", ["shuffle", "sequential"])
+def test_outputs_beyond_four_gib_statewide(statewide_series, order_name):
+    # 128 batches of 32 in one call: out_x alone is 4.39 GB, so sample offsets cross 2^31 and 2^32
+    # bytes.  Samples at the start, straddling both boundaries, and at the end are checked.
+    w = workloads.WORKLOADS["statewide"]
+    mean, std = _sampled_stats(statewide_series)
+    k = 128
+    sample_bytes = w.P * w.N * w.F * 4
+    picks = sorted({0, 1, 2 ** 31 // sample_bytes, 2 ** 31 // sample_bytes + 1, 2 ** 32 // sample_bytes,
+                    2 ** 32 // sample_bytes + 1, k * w.B - 1})
+    assert picks[-1] * sample_bytes > 2 ** 32
+    with pgti.Context(0) as ctx:
+        ctx.load_series(statewide_series, w.P, w.Q, w.B, pgti.PGTI_F32, mean, std)
+        ctx.epoch_indices_ex(ORDERS[order_name], seed=5, epoch=2)
+        share = ctx.get_indices()
+        x = torch.full((k * w.B, w.P, w.N, w.F), float("nan"), dtype=torch.float32, device="cuda")
+        y = torch.full((k * w.B, w.Q, w.N, w.F), float("nan"), dtype=torch.float32, device="cuda")
+        first = 7
+        assert ctx.build_batches(first, k, x, y) == k * w.B
+        torch.cuda.synchronize()
+        for j in picks:
+            start = share[first * w.B + j:first * w.B + j + 1]
+            wx, wy = oracle.build_batch(statewide_series, oracle.F32, w.P, w.Q, mean, std, start)
+            assert _bits_equal(x[j].cpu().numpy(), wx[0]) and _bits_equal(y[j].cpu().numpy(), wy[0]), j
+        del x, y
+    torch.cuda.empty_cache()
+
+
 # ----------------------------------------------------------------------------------------------
 # statistics computed by the library
 # ----------------------------------------------------------------------------------------------
