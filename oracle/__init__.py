@@ -202,9 +202,11 @@ def standardize(v: float, mu: float, sigma: float) -> float:
 
 
 def build_batch(series: np.ndarray, storage: int, P: int, Q: int, mean, std,
-                starts) -> tuple[np.ndarray, np.ndarray]:
+                starts, out=None) -> tuple[np.ndarray, np.ndarray]:
     """x[count,P,N,F], y[count,Q,N,F] for the given starts.  `series` is [T,N,F], float32 for
-    storage F32 or uint16 bf16 bit patterns for storage BF16."""
+    storage F32 or uint16 bf16 bit patterns for storage BF16.  `out` = (x, y) float32 C-contiguous
+    arrays with at least that many elements receives the result in place of fresh arrays (callers
+    that check many batches reuse their buffers); the returned views have the shapes above."""
     want = np.float32 if storage == F32 else np.uint16
     if series.dtype != want or not series.flags.c_contiguous or series.ndim != 3:
         raise ValueError("series must be a C-contiguous [T,N,F] array of the storage dtype")
@@ -214,16 +216,24 @@ def build_batch(series: np.ndarray, storage: int, P: int, Q: int, mean, std,
     if mean.shape != (F,) or std.shape != (F,):
         raise ValueError("mean/std must have F entries")
     count = starts.shape[0]
-    x = np.empty((count, P, N, F), dtype=np.float32)
-    y = np.empty((count, Q, N, F), dtype=np.float32)
+    if out is None:
+        x = np.empty((count, P, N, F), dtype=np.float32)
+        y = np.empty((count, Q, N, F), dtype=np.float32)
+    else:
+        bx, by = out
+        for b, steps in ((bx, P), (by, Q)):
+            if b.dtype != np.float32 or not b.flags.c_contiguous or b.size < count * steps * N * F:
+                raise ValueError("out buffers must be C-contiguous float32 with room for the batch")
+        x = bx.reshape(-1)[:count * P * N * F].reshape(count, P, N, F)
+        y = by.reshape(-1)[:count * Q * N * F].reshape(count, Q, N, F)
     _check(_load().oracle_build_batch(_ptr(series), storage, T, N, F, P, Q, _ptr(mean), _ptr(std),
                                       _ptr(starts), count, _ptr(x), _ptr(y)), "build_batch")
     return x, y
 
 
 def build_batch_bf16_out(series: np.ndarray, storage: int, P: int, Q: int, mean, std,
-                         starts) -> tuple[np.ndarray, np.ndarray]:
-    """Like build_batch, outputs as uint16 bf16 bit patterns."""
+                         starts, out=None) -> tuple[np.ndarray, np.ndarray]:
+    """Like build_batch, outputs as uint16 bf16 bit patterns (`out` buffers are uint16 then)."""
     want = np.float32 if storage == F32 else np.uint16
     if series.dtype != want or not series.flags.c_contiguous or series.ndim != 3:
         raise ValueError("series must be a C-contiguous [T,N,F] array of the storage dtype")
@@ -231,8 +241,16 @@ def build_batch_bf16_out(series: np.ndarray, storage: int, P: int, Q: int, mean,
     mean, std = _c(mean, np.float32), _c(std, np.float32)
     starts = _c(starts, np.int32)
     count = starts.shape[0]
-    x = np.empty((count, P, N, F), dtype=np.uint16)
-    y = np.empty((count, Q, N, F), dtype=np.uint16)
+    if out is None:
+        x = np.empty((count, P, N, F), dtype=np.uint16)
+        y = np.empty((count, Q, N, F), dtype=np.uint16)
+    else:
+        bx, by = out
+        for b, steps in ((bx, P), (by, Q)):
+            if b.dtype != np.uint16 or not b.flags.c_contiguous or b.size < count * steps * N * F:
+                raise ValueError("out buffers must be C-contiguous uint16 with room for the batch")
+        x = bx.reshape(-1)[:count * P * N * F].reshape(count, P, N, F)
+        y = by.reshape(-1)[:count * Q * N * F].reshape(count, Q, N, F)
     _check(_load().oracle_build_batch_bf16_out(_ptr(series), storage, T, N, F, P, Q, _ptr(mean), _ptr(std),
                                                _ptr(starts), count, _ptr(x), _ptr(y)), "build_batch_bf16_out")
     return x, y

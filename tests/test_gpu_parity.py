@@ -135,6 +135,96 @@ def test_statewide_indices_and_sampled_batches(statewide_series):
     _run_workload_epoch(w, statewide_series, batches=_sampled)
 
 
+def _whole_epochs_every_batch(w, series, order, out_bf16, epochs):
+    """Every batch of full-size epochs, bit for bit: the device builds 16 batches per call and
+    copies them to pinned memory while 16 host threads run the oracle on the previous 16 and compare
+    bytes.  Returns the number of batches checked."""
+    import concurrent.futures as cf
+    import ctypes
+    import threading
+
+    mean, std = _sampled_stats(series)
+    storage = pgti.PGTI_F32 if w.storage == "f32" else pgti.PGTI_BF16
+    ser_o = _oracle_series(series, storage)
+    k, workers = 16, 16
+    memcmp = ctypes.CDLL(None).memcmp
+    memcmp.restype = ctypes.c_int
+    memcmp.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t]
+    local = threading.local()
+    np_out, t_out = (np.uint16, torch.bfloat16) if out_bf16 else (np.float32, torch.float32)
+    oracle_build = oracle.build_batch_bf16_out if out_bf16 else oracle.build_batch
+
+    def check(host_x, host_y, j, starts):
+        # host_x / host_y: numpy views of the pinned chunk; j: batch number inside the chunk
+        if not hasattr(local, "x"):
+            local.x = np.empty((w.B, w.P, w.N, w.F), np_out)
+            local.y = np.empty((w.B, w.Q, w.N, w.F), np_out)
+        wx, wy = oracle_build(ser_o, storage, w.P, w.Q, mean, std, starts, out=(local.x, local.y))
+        gx, gy = host_x[j * w.B:j * w.B + len(starts)], host_y[j * w.B:j * w.B + len(starts)]
+        return (memcmp(gx.ctypes.data, wx.ctypes.data, wx.nbytes) == 0 and
+                memcmp(gy.ctypes.data, wy.ctypes.data, wy.nbytes) == 0)
+
+    def as_numpy(t):
+        return t.view(torch.int16).numpy().view(np.uint16) if out_bf16 else t.numpy()
+
+    checked = 0
+    with pgti.Context(0) as ctx, cf.ThreadPoolExecutor(workers) as pool:
+        ctx.load_series(series, w.P, w.Q, w.B, storage, mean, std)
+        dev = [(torch.empty((k * w.B, w.P, w.N, w.F), dtype=t_out, device="cuda"),
+                torch.empty((k * w.B, w.Q, w.N, w.F), dtype=t_out, device="cuda")) for _ in range(2)]
+        host = [(torch.empty((k * w.B, w.P, w.N, w.F), dtype=t_out, pin_memory=True),
+                 torch.empty((k * w.B, w.Q, w.N, w.F), dtype=t_out, pin_memory=True)) for _ in range(2)]
+        done = [torch.cuda.Event(), torch.cuda.Event()]
+        pending = [[], []]
+
+        def collect(slot):
+            nonlocal checked
+            for fut, where in pending[slot]:  # the host buffers of this slot are free once compared
+                assert fut.result(), f"epoch/batch {where} differs from the oracle"
+                checked += 1
+            pending[slot] = []
+
+        chunk = 0
+        for epoch in epochs:
+            n_share = ctx.epoch_indices_ex(order, seed=w.seed, epoch=epoch, rank=w.rank, world=w.world)
+            share = ctx.get_indices()
+            want = oracle.epoch_indices_ex(order, w.n_windows, 0, w.n_windows, w.B, w.seed, epoch, w.rank, w.world)
+            assert n_share == len(want) and np.array_equal(share, want)
+            nb = ctx.num_batches()
+            for first in range(0, nb, k):
+                slot = chunk & 1
+                chunk += 1
+                collect(slot)
+                kk = min(k, nb - first)
+                build = ctx.build_batches_bf16 if out_bf16 else ctx.build_batches
+                build(first, kk, dev[slot][0], dev[slot][1])
+                host[slot][0].copy_(dev[slot][0], non_blocking=True)
+                host[slot][1].copy_(dev[slot][1], non_blocking=True)
+                done[slot].record()
+                done[slot].synchronize()
+                hx, hy = as_numpy(host[slot][0]), as_numpy(host[slot][1])
+                pending[slot] = [(pool.submit(check, hx, hy, j, want[(first + j) * w.B:(first + j + 1) * w.B]),
+                                  (epoch, first + j)) for j in range(kk)]
+        collect(0)
+        collect(1)
+    return checked
+
+
+@pytest.mark.parametrize("order_name,out_bf16", [("shuffle", False), ("sequential", False),
+                                                 ("batch_shuffle", False), ("shuffle", True)])
+def test_statewide_whole_epoch_every_batch(statewide_series, order_name, out_bf16):
+    # all 3,285 batches of the full-size epoch (225 GB of fp32 outputs), for every order (the
+    # shuffle runs the span kernel, the other two the row-centric kernel) and for bf16 outputs
+    w = workloads.WORKLOADS["statewide"]
+    assert _whole_epochs_every_batch(w, statewide_series, ORDERS[order_name], out_bf16, w.epochs) == 3285
+
+
+def test_statewide_bf16_rank3of16_every_batch_three_epochs(statewide_series):
+    # bf16 storage, rank 3 of 16: all 206 batches of each of the three epochs
+    w = workloads.WORKLOADS["statewide_bf16_rank3of16"]
+    assert _whole_epochs_every_batch(w, statewide_series, ORDERS["shuffle"], False, w.epochs) == 3 * 206
+
+
 def test_statewide_bf16_rank3of16_three_epochs(statewide_series):
     w = workloads.WORKLOADS["statewide_bf16_rank3of16"]
     _run_workload_epoch(w, statewide_series, batches=lambda nb: [0, nb // 2, nb - 1])
