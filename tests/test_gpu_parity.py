@@ -839,6 +839,25 @@ def test_on_device_algorithm1_statistics(storage_name, fraction):
         assert all(_ulp_close(g, o) for g, o in zip(list(got_m) + list(got_s), list(om) + list(os_)))
 
 
+def test_on_device_statistics_large_slab(statewide_series):
+    # The first 40,000 entries of the Statewide series (3.6 GB): the training windows hold 7.5e9
+    # values, past 2^32, so element counts and weights must be 64-bit all the way.
+    w = workloads.WORKLOADS["statewide"]
+    T = 40000
+    slab = statewide_series[:T]
+    assert 0.7 * (T - w.P - w.Q + 1) * w.P * w.N * w.F > 2 ** 32
+    want_m, want_s = oracle.alg1_train_stats_fraction(slab, w.P, w.Q, 0.7)
+    om, os_ = oracle.series_stats(slab)
+    with pgti.Context(0) as ctx:
+        ctx.load_series_ex(slab, w.P, w.Q, w.B, pgti.PGTI_F32, stats_rule=pgti.PGTI_STATS_ALG1_TRAIN,
+                           train_fraction=0.7)
+        got_m, got_s = ctx.get_stats()
+        assert _ulp_close(got_m[0], want_m) and _ulp_close(got_s[0], want_s), (got_m, want_m, got_s, want_s)
+        ctx.load_series_ex(slab, w.P, w.Q, w.B, pgti.PGTI_BF16, stats_rule=pgti.PGTI_STATS_FEATURE_GLOBAL)
+        got_m, got_s = ctx.get_stats()
+        assert all(_ulp_close(g, o) for g, o in zip(list(got_m) + list(got_s), list(om) + list(os_)))
+
+
 def test_load_ex_argument_errors():
     series = np.zeros((40, 3, 1), np.float32)
     with pgti.Context(0) as ctx:
