@@ -132,8 +132,8 @@ int pgti_get_stats(pgti_ctx* c, float* mean_out, float* std_out);
  *
  * The epoch order is the list of starts 0..n-1 sorted ascending by (key_i, i), where
  * key_i = M((h1 ^ i) + g), h1 = M((h0 ^ epoch) + g), h0 = M(seed + g), M the splitmix64 output
- * function and g = 0x9E3779B97F4A7C15; computed on the device with a stable least-significant-
- * digit radix sort.  Rank `rank` of `world` owns order[lo, hi), lo = floor(rank*n/world),
+ * function and g = 0x9E3779B97F4A7C15; computed on the device (the pairs are all distinct, so
+ * the order is unique whatever sorting method produces it).  Rank `rank` of `world` owns order[lo, hi), lo = floor(rank*n/world),
  * hi = floor((rank+1)*n/world): no padding, no dropping.  *n_share (HOST, may be NULL)
  * receives hi - lo.  Same arguments give the same bits on every run.
  * Replaces the previous share.  Stream ordering is handled inside: the sort waits for batch

@@ -3,26 +3,26 @@
 //
 // The shuffle is defined as the order of the starts 0..n-1 under ascending (key_i, i), with
 // key_i = M((h1 ^ i) + g), h1 = M((h0 ^ epoch) + g), h0 = M(seed + g), M the splitmix64 output
-// function.  It is computed with a least-significant-digit radix sort: 8 stable counting passes
-// over 8-bit digits of the 64-bit key, the start index riding along as the value.  Stability of
-// every pass makes the index the tiebreak.
+// function.
 //
-// With at most 256 tiles (n <= 524,288 keys, every benchmark workload) a pass is ONE launch: the
-// count table is tile-major, each scatter workgroup sums the columns of the tiles before it by
-// itself (a coalesced walk over at most 256 rows), counts the next pass's digits into a second
-// table and clears its row of a third one for the pass after that.  Larger n:
-// One pass = two launches:
+// Three ways to get that order, by the number of keys n:
+//   n <= 4,096       one launch of one workgroup: keys are generated into LDS and ordered by
+//                    (key, index) with a bitonic network.
+//   n <= 1,048,576   (every benchmark workload) three launches: count the keys per bucket of the top
+//                    4..10 key bits; scatter every (key, index) into its bucket (place inside the
+//                    bucket arbitrary: LDS and global integer atomics); one workgroup per bucket
+//                    orders its few hundred pairs in LDS, again by (key, index).  The pairs are all
+//                    distinct, so the result does not depend on the order the atomics resolved in.
+//   larger n         a least-significant-digit radix sort: 8 stable counting passes over 8-bit
+//                    digits, the index riding along as the value (stability of every pass makes the
+//                    index the tiebreak).  One pass = two launches:
 //   scan    : exclusive prefix over workgroups of the per-(digit, workgroup) counts, digit totals
 //   scatter : each workgroup ranks its tile (wave ballots give every key its rank among equal
 //             digits in its wave; per-wave LDS counters chain the rounds), adds the scanned base
 //             and writes key/value to the destination; while doing so it counts the NEXT pass's
 //             digit of every key into the count table of the destination tile (integer atomics,
 //             order independent), so no separate counting launch is needed.
-// The key generation launch also produces the counts of pass 0.
-//
-// Up to 4096 keys (small datasets, validation and test ranges, batch-level shuffles) the whole order
-// comes from ONE launch of one workgroup: keys are generated into LDS and ordered by (key, index)
-// with a bitonic network; (key, index) pairs are all distinct, so the result is the same order.
+//   The key generation launch also produces the counts of pass 0.
 //
 // Other orders reuse the same machinery: the sequential order (validation / test passes over a
 // range of starts, Sec. 3.1) is an iota; the batch-level shuffle of Sec. 5.4 (fixed partition,
@@ -38,7 +38,6 @@ constexpr uint32_t kWave = 64;
 constexpr uint32_t kWaves = kThreads / kWave;
 constexpr uint32_t kItems = kSortTile / kThreads;  // rounds per wave: 8
 constexpr uint32_t kRadix = 256;
-constexpr uint32_t kFusedScanTiles = 256;  // up to this many tiles a scatter workgroup scans the counts itself
 constexpr uint64_t kGamma = 0x9E3779B97F4A7C15ull;
 static_assert(kRadix == kThreads, "one thread per digit in the scan steps");
 static_assert(kItems * kThreads == kSortTile, "tile must be a whole number of rounds");
@@ -68,12 +67,10 @@ __device__ __forceinline__ uint32_t block_inclusive_scan(uint32_t v, uint32_t* l
 
 // keys[i] = key(seed, epoch, counter_base + i*counter_stride) for i < n; counts of the lowest digit
 // per (digit, workgroup) into hist0[digit][wg].
-// TILE_MAJOR: counts go to hist0[wg][digit] and this workgroup's row of hist1 is cleared.
-template <bool TILE_MAJOR>
 __global__ void __launch_bounds__(kThreads) keygen_kernel(uint64_t seed, uint64_t epoch, uint32_t n,
                                                           uint32_t nblk, uint64_t counter_base,
                                                           uint64_t counter_stride, uint64_t* keys,
-                                                          uint32_t* hist0, uint32_t* hist1) {
+                                                          uint32_t* hist0) {
     __shared__ uint32_t counts[kRadix];
     const uint32_t tid = threadIdx.x, b = blockIdx.x;
     counts[tid] = 0;
@@ -90,12 +87,7 @@ __global__ void __launch_bounds__(kThreads) keygen_kernel(uint64_t seed, uint64_
         }
     }
     __syncthreads();
-    if constexpr (TILE_MAJOR) {
-        hist0[b * kRadix + tid] = counts[tid];
-        hist1[b * kRadix + tid] = 0u;
-    } else {
-        hist0[tid * nblk + b] = counts[tid];
-    }
+    hist0[tid * nblk + b] = counts[tid];
 }
 
 // One workgroup per digit d: hist[d][0..nblk) becomes its exclusive prefix, tot[d] its sum.
@@ -128,16 +120,12 @@ __global__ void __launch_bounds__(kThreads) scan_kernel(uint32_t* hist, uint32_t
 // FIRST: values are the element positions themselves (no value array yet).
 // LAST : only the values whose destination falls in [lo, hi) are written, to share[pos - lo],
 //        with value_offset added (the first start of the range the positions refer to).
-// FUSED: `hist_scanned` holds RAW tile-major counts [tile][digit]; the prefix over earlier tiles and
-//        the digit totals are summed here, `hist_next` is tile-major too and `hist_clear` (the
-//        table of the pass after next) gets this workgroup's row zeroed.  `tot` is unused.
-template <bool FIRST, bool LAST, bool FUSED>
+template <bool FIRST, bool LAST>
 __global__ void __launch_bounds__(kThreads) scatter_kernel(
     const uint64_t* __restrict__ keys_in, const int32_t* __restrict__ vals_in,
     uint64_t* __restrict__ keys_out, int32_t* __restrict__ vals_out,
     const uint32_t* __restrict__ hist_scanned, const uint32_t* __restrict__ tot,
-    uint32_t* __restrict__ hist_next, uint32_t* __restrict__ hist_clear, uint32_t n, uint32_t nblk,
-    uint32_t shift, int32_t* __restrict__ share, uint32_t lo, uint32_t hi, int32_t value_offset) {
+    uint32_t* __restrict__ hist_next, uint32_t n, uint32_t nblk, uint32_t shift, int32_t* __restrict__ share, uint32_t lo, uint32_t hi, int32_t value_offset) {
     __shared__ uint32_t wave_counts[kWaves][kRadix];  // running counts, later wave-exclusive offsets
     __shared__ uint32_t digit_base[kRadix];
     __shared__ uint32_t scan_tmp[kThreads];
@@ -195,28 +183,8 @@ __global__ void __launch_bounds__(kThreads) scatter_kernel(
             wave_counts[k][tid] = run;
             run += cnt;
         }
-        uint32_t t, before;
-        if constexpr (FUSED) {
-            t = 0;
-            before = 0;
-            // Coalesced: 256 consecutive counts per tile.  16 independent loads are issued before
-            // the first is used, otherwise the walk costs one L2 latency per tile.
-            for (uint32_t base = 0; base < nblk; base += 16) {
-                uint32_t cnt[16];
-#pragma unroll
-                for (uint32_t u = 0; u < 16; ++u)
-                    cnt[u] = (base + u < nblk) ? hist_scanned[(base + u) * kRadix + tid] : 0u;
-#pragma unroll
-                for (uint32_t u = 0; u < 16; ++u) {
-                    t += cnt[u];
-                    before += (base + u < b) ? cnt[u] : 0u;
-                }
-            }
-            hist_clear[b * kRadix + tid] = 0u;
-        } else {
-            t = tot[tid];
-            before = hist_scanned[static_cast<size_t>(tid) * nblk + b];
-        }
+        const uint32_t t = tot[tid];
+        const uint32_t before = hist_scanned[static_cast<size_t>(tid) * nblk + b];
         const uint32_t incl = block_inclusive_scan(t, scan_tmp);
         digit_base[tid] = (incl - t) + before;
     }
@@ -233,8 +201,7 @@ __global__ void __launch_bounds__(kThreads) scatter_kernel(
             keys_out[pos] = key[r];
             vals_out[pos] = val[r];
             const uint32_t dn = static_cast<uint32_t>(key[r] >> (shift + 8)) & 0xFFu;
-            if constexpr (FUSED) atomicAdd(&hist_next[(pos / kSortTile) * kRadix + dn], 1u);
-            else atomicAdd(&hist_next[static_cast<size_t>(dn) * nblk + pos / kSortTile], 1u);
+            atomicAdd(&hist_next[static_cast<size_t>(dn) * nblk + pos / kSortTile], 1u);
         } else {
             if (pos >= lo && pos < hi) share[pos - lo] = val[r] + value_offset;
         }
@@ -283,6 +250,155 @@ __global__ void __launch_bounds__(kSmallSortThreads) small_sort_kernel(uint64_t 
         if (i >= lo && i < hi) share[i - lo] = static_cast<int32_t>(idx[i]) + value_offset;
 }
 
+// ---- bucket path: count, scatter, one workgroup per bucket --------------------------------------
+// Bucket of a key = its top `dbits` bits, D = 2^dbits <= kMaxBuckets buckets.  tot[], cursor[] (D
+// entries each) are zero between sorts: the last kernel clears what the first two filled.
+constexpr uint32_t kBucketBins = kMaxSortBuckets / kThreads;  // bins per thread in the offset scan: 4
+static_assert(kBucketBins * kThreads == kMaxSortBuckets, "whole bins per thread");
+
+__device__ __forceinline__ uint64_t epoch_key(uint64_t h1, uint64_t counter) { return mix64((h1 ^ counter) + kGamma); }
+
+__global__ void __launch_bounds__(kThreads) bucket_count_kernel(uint64_t seed, uint64_t epoch, uint32_t n,
+                                                                uint64_t counter_base, uint64_t counter_stride,
+                                                                uint32_t dbits, uint32_t* __restrict__ tot) {
+    __shared__ uint32_t hist[kMaxSortBuckets];
+    const uint32_t tid = threadIdx.x, D = 1u << dbits;
+    for (uint32_t bin = tid; bin < D; bin += kThreads) hist[bin] = 0;
+    __syncthreads();
+    const uint64_t h1 = mix64((mix64(seed + kGamma) ^ epoch) + kGamma);
+#pragma unroll
+    for (uint32_t it = 0; it < kItems; ++it) {
+        const uint32_t i = blockIdx.x * kSortTile + it * kThreads + tid;
+        if (i < n) atomicAdd(&hist[epoch_key(h1, counter_base + i * counter_stride) >> (64 - dbits)], 1u);
+    }
+    __syncthreads();
+    for (uint32_t bin = tid; bin < D; bin += kThreads) {
+        const uint32_t cnt = hist[bin];
+        if (cnt) atomicAdd(&tot[bin], cnt);
+    }
+}
+
+// Writes (key, index) of every element of the tile into its bucket: bucket b occupies
+// [off[b], off[b+1]) of keys_out / vals_out, off = exclusive prefix of tot (recomputed by every
+// workgroup; workgroup 0 also stores it, with off[D] = n, for the next kernel).
+__global__ void __launch_bounds__(kThreads) bucket_scatter_kernel(uint64_t seed, uint64_t epoch, uint32_t n,
+                                                                  uint64_t counter_base, uint64_t counter_stride,
+                                                                  uint32_t dbits, const uint32_t* __restrict__ tot,
+                                                                  uint32_t* __restrict__ cursor,
+                                                                  uint32_t* __restrict__ off,
+                                                                  uint64_t* __restrict__ keys_out,
+                                                                  int32_t* __restrict__ vals_out) {
+    __shared__ uint32_t hist[kMaxSortBuckets];  // count of this tile per bucket
+    __shared__ uint32_t base[kMaxSortBuckets];  // where this tile's share of the bucket starts
+    __shared__ uint32_t scan_tmp[kThreads];
+    const uint32_t tid = threadIdx.x, D = 1u << dbits;
+    for (uint32_t bin = tid; bin < D; bin += kThreads) hist[bin] = 0;
+    __syncthreads();
+    const uint64_t h1 = mix64((mix64(seed + kGamma) ^ epoch) + kGamma);
+    uint64_t key[kItems];
+    uint32_t rank[kItems];
+#pragma unroll
+    for (uint32_t it = 0; it < kItems; ++it) {
+        const uint32_t i = blockIdx.x * kSortTile + it * kThreads + tid;
+        key[it] = epoch_key(h1, counter_base + i * counter_stride);
+        rank[it] = (i < n) ? atomicAdd(&hist[key[it] >> (64 - dbits)], 1u) : 0u;
+    }
+    // offsets of the buckets: thread tid owns bins [4 tid, 4 tid + 4)
+    uint32_t t[kBucketBins], sum = 0;
+#pragma unroll
+    for (uint32_t u = 0; u < kBucketBins; ++u) {
+        const uint32_t bin = tid * kBucketBins + u;
+        t[u] = (bin < D) ? tot[bin] : 0u;
+        sum += t[u];
+    }
+    uint32_t run = block_inclusive_scan(sum, scan_tmp) - sum;  // the scan's barriers also complete hist[]
+#pragma unroll
+    for (uint32_t u = 0; u < kBucketBins; ++u) {
+        const uint32_t bin = tid * kBucketBins + u;
+        if (bin < D) {
+            const uint32_t cnt = hist[bin];
+            if (cnt) base[bin] = run + atomicAdd(&cursor[bin], cnt);
+            if (blockIdx.x == 0) off[bin] = run;
+        }
+        run += t[u];
+    }
+    if (blockIdx.x == 0 && tid == 0) off[D] = n;
+    __syncthreads();
+#pragma unroll
+    for (uint32_t it = 0; it < kItems; ++it) {
+        const uint32_t i = blockIdx.x * kSortTile + it * kThreads + tid;
+        if (i >= n) continue;
+        const uint32_t pos = base[key[it] >> (64 - dbits)] + rank[it];
+        if (pos >= n) continue;  // cannot happen with consistent counts; never write out of bounds
+        keys_out[pos] = key[it];
+        vals_out[pos] = static_cast<int32_t>(i);
+    }
+}
+
+// Workgroup b orders bucket b by (key, index) and writes the indices whose final position falls in
+// [lo, hi) to share[pos - lo], plus value_offset.  Up to `cap` <= kBucketSortKeys pairs the bucket is
+// ordered in LDS with a bitonic network (padding: largest key with an index above every real one);
+// a larger bucket takes the slow way, the rank of every pair counted against the whole bucket.
+__global__ void __launch_bounds__(kThreads) bucket_sort_kernel(const uint64_t* __restrict__ keys,
+                                                               const int32_t* __restrict__ vals,
+                                                               const uint32_t* __restrict__ off,
+                                                               uint32_t* __restrict__ tot,
+                                                               uint32_t* __restrict__ cursor, uint32_t n,
+                                                               uint32_t cap, int32_t* __restrict__ share, uint32_t lo,
+                                                               uint32_t hi, int32_t value_offset) {
+    __shared__ uint64_t key[kBucketSortKeys];
+    __shared__ uint32_t idx[kBucketSortKeys];
+    const uint32_t tid = threadIdx.x, b = blockIdx.x;
+    const uint32_t end = min(off[b + 1], n), begin = min(off[b], end), m = end - begin;  // never past the arrays
+    if (tid == 0) {
+        tot[b] = 0;
+        cursor[b] = 0;
+    }
+    if (m == 0) return;
+    if (m <= cap) {
+        uint32_t m2 = 2;
+        while (m2 < m) m2 <<= 1;
+        for (uint32_t i = tid; i < m2; i += kThreads) {
+            key[i] = (i < m) ? keys[begin + i] : ~0ull;
+            idx[i] = (i < m) ? static_cast<uint32_t>(vals[begin + i]) : 0xFFFFFFFFu;
+        }
+        __syncthreads();
+        for (uint32_t size = 2; size <= m2; size <<= 1) {
+            for (uint32_t stride = size >> 1; stride > 0; stride >>= 1) {
+                for (uint32_t t = tid; t < (m2 >> 1); t += kThreads) {
+                    const uint32_t a = ((t & ~(stride - 1)) << 1) | (t & (stride - 1));
+                    const uint32_t c = a + stride;
+                    const uint64_t ka = key[a], kc = key[c];
+                    const uint32_t ia = idx[a], ic = idx[c];
+                    const bool a_after_c = (ka > kc) || (ka == kc && ia > ic);
+                    const bool ascending = (a & size) == 0;
+                    if (a_after_c == ascending) {
+                        key[a] = kc; key[c] = ka;
+                        idx[a] = ic; idx[c] = ia;
+                    }
+                }
+                __syncthreads();
+            }
+        }
+        for (uint32_t i = tid; i < m; i += kThreads) {
+            const uint32_t pos = begin + i;
+            if (pos >= lo && pos < hi) share[pos - lo] = static_cast<int32_t>(idx[i]) + value_offset;
+        }
+    } else {
+        for (uint32_t e = tid; e < m; e += kThreads) {
+            const uint64_t k = keys[begin + e];
+            const int32_t v = vals[begin + e];
+            uint32_t below = 0;
+            for (uint32_t f = 0; f < m; ++f) {
+                const uint64_t k2 = keys[begin + f];
+                below += (k2 < k) || (k2 == k && vals[begin + f] < v);
+            }
+            const uint32_t pos = begin + below;
+            if (pos >= lo && pos < hi) share[pos - lo] = v + value_offset;
+        }
+    }
+}
+
 // share[i] = first + i (sequential order).
 __global__ void __launch_bounds__(kThreads) iota_kernel(int32_t* __restrict__ share, uint32_t len, int32_t first) {
     const uint32_t i = blockIdx.x * kThreads + threadIdx.x;
@@ -305,26 +421,22 @@ __global__ void __launch_bounds__(kThreads) expand_batches_kernel(const int32_t*
 
 namespace {
 
-template <bool FUSED>
 void launch_pass(pgti_ctx* c, uint32_t pass, uint32_t n, uint32_t nblk, const SortPlan& plan, uint32_t* hist,
-                 uint32_t* hist_next, uint32_t* hist_clear, hipStream_t s) {
+                 uint32_t* hist_next, hipStream_t s) {
     const uint64_t* kin = c->d_keys[pass & 1];
     const int32_t* vin = c->d_vals[pass & 1];
     uint64_t* kout = c->d_keys[(pass + 1) & 1];
     int32_t* vout = c->d_vals[(pass + 1) & 1];
     const dim3 grid(nblk), block(kThreads);
     if (pass == 0)
-        hipLaunchKernelGGL((scatter_kernel<true, false, FUSED>), grid, block, 0, s, kin, vin, kout, vout, hist, c->d_tot,
-                           hist_next, hist_clear, n, nblk, 8 * pass, plan.out, plan.out_lo, plan.out_hi,
-                           plan.value_offset);
+        hipLaunchKernelGGL((scatter_kernel<true, false>), grid, block, 0, s, kin, vin, kout, vout, hist, c->d_tot,
+                           hist_next, n, nblk, 8 * pass, plan.out, plan.out_lo, plan.out_hi, plan.value_offset);
     else if (pass < 7)
-        hipLaunchKernelGGL((scatter_kernel<false, false, FUSED>), grid, block, 0, s, kin, vin, kout, vout, hist, c->d_tot,
-                           hist_next, hist_clear, n, nblk, 8 * pass, plan.out, plan.out_lo, plan.out_hi,
-                           plan.value_offset);
+        hipLaunchKernelGGL((scatter_kernel<false, false>), grid, block, 0, s, kin, vin, kout, vout, hist, c->d_tot,
+                           hist_next, n, nblk, 8 * pass, plan.out, plan.out_lo, plan.out_hi, plan.value_offset);
     else
-        hipLaunchKernelGGL((scatter_kernel<false, true, FUSED>), grid, block, 0, s, kin, vin, kout, vout, hist, c->d_tot,
-                           hist_next, hist_clear, n, nblk, 8 * pass, plan.out, plan.out_lo, plan.out_hi,
-                           plan.value_offset);
+        hipLaunchKernelGGL((scatter_kernel<false, true>), grid, block, 0, s, kin, vin, kout, vout, hist, c->d_tot,
+                           hist_next, n, nblk, 8 * pass, plan.out, plan.out_lo, plan.out_hi, plan.value_offset);
 }
 
 }  // namespace
@@ -341,22 +453,29 @@ hipError_t launch_sorted_order(pgti_ctx* c, uint64_t seed, uint64_t epoch, const
         return hipGetLastError();
     }
     const uint32_t nblk = (n + kSortTile - 1) / kSortTile;
-    if (nblk <= kFusedScanTiles) {
-        // 1 + 8 launches; three count tables rotate: read / count the next pass / cleared for the one after.
-        hipLaunchKernelGGL(keygen_kernel<true>, dim3(nblk), dim3(kThreads), 0, s, seed, epoch, n, nblk,
-                           plan.counter_base, plan.counter_stride, c->d_keys[0], c->d_hist[0], c->d_hist[1]);
-        for (uint32_t pass = 0; pass < 8; ++pass)
-            launch_pass<true>(c, pass, n, nblk, plan, c->d_hist[pass % 3], c->d_hist[(pass + 1) % 3],
-                              c->d_hist[(pass + 2) % 3], s);
-    } else {
-        hipLaunchKernelGGL(keygen_kernel<false>, dim3(nblk), dim3(kThreads), 0, s, seed, epoch, n, nblk,
-                           plan.counter_base, plan.counter_stride, c->d_keys[0], c->d_hist[0], c->d_hist[1]);
-        for (uint32_t pass = 0; pass < 8; ++pass) {
-            uint32_t* hist = c->d_hist[pass & 1];
-            uint32_t* hist_next = c->d_hist[(pass + 1) & 1];
-            hipLaunchKernelGGL(scan_kernel, dim3(kRadix), dim3(kThreads), 0, s, hist, c->d_tot, hist_next, nblk);
-            launch_pass<false>(c, pass, n, nblk, plan, hist, hist_next, nullptr, s);
-        }
+    if (n <= kBucketPathKeys) {
+        // buckets of a few hundred keys: the fewest top bits that bring the average to 384 or less
+        uint32_t dbits = 4;
+        while ((1u << dbits) < kMaxSortBuckets && (n >> dbits) > 384u) ++dbits;
+        const uint32_t D = 1u << dbits;
+        uint32_t* tot = c->d_bucket;
+        uint32_t* cursor = c->d_bucket + kMaxSortBuckets;
+        uint32_t* off = c->d_bucket + 2 * kMaxSortBuckets;
+        hipLaunchKernelGGL(bucket_count_kernel, dim3(nblk), dim3(kThreads), 0, s, seed, epoch, n, plan.counter_base,
+                           plan.counter_stride, dbits, tot);
+        hipLaunchKernelGGL(bucket_scatter_kernel, dim3(nblk), dim3(kThreads), 0, s, seed, epoch, n, plan.counter_base,
+                           plan.counter_stride, dbits, tot, cursor, off, c->d_keys[1], c->d_vals[1]);
+        hipLaunchKernelGGL(bucket_sort_kernel, dim3(D), dim3(kThreads), 0, s, c->d_keys[1], c->d_vals[1], off, tot,
+                           cursor, n, c->bucket_sort_cap, plan.out, plan.out_lo, plan.out_hi, plan.value_offset);
+        return hipGetLastError();
+    }
+    hipLaunchKernelGGL(keygen_kernel, dim3(nblk), dim3(kThreads), 0, s, seed, epoch, n, nblk, plan.counter_base,
+                       plan.counter_stride, c->d_keys[0], c->d_hist[0]);
+    for (uint32_t pass = 0; pass < 8; ++pass) {
+        uint32_t* hist = c->d_hist[pass & 1];
+        uint32_t* hist_next = c->d_hist[(pass + 1) & 1];
+        hipLaunchKernelGGL(scan_kernel, dim3(kRadix), dim3(kThreads), 0, s, hist, c->d_tot, hist_next, nblk);
+        launch_pass(c, pass, n, nblk, plan, hist, hist_next, s);
     }
     return hipGetLastError();
 }

@@ -3,6 +3,7 @@
 // series_store.hip, epoch_sort.hip and batch_gather.hip.
 #include <stdarg.h>
 #include <stdio.h>
+#include <stdlib.h>
 #include <string.h>
 
 #include <cmath>
@@ -45,8 +46,8 @@ void free_series(pgti_ctx* c) {
     drop(c->d_vals[1]);
     drop(c->d_hist[0]);
     drop(c->d_hist[1]);
-    drop(c->d_hist[2]);
     drop(c->d_tot);
+    drop(c->d_bucket);
     drop(c->d_share);
     c->loaded = false;
     c->have_share = false;
@@ -181,8 +182,9 @@ int load_impl(pgti_ctx* c, const float* src, const pgti_load_spec* spec) {
     if (int rc = alloc(&c->d_vals[1], sizeof(int32_t) * n)) return rc;
     if (int rc = alloc(&c->d_hist[0], sizeof(uint32_t) * 256 * nblk)) return rc;
     if (int rc = alloc(&c->d_hist[1], sizeof(uint32_t) * 256 * nblk)) return rc;
-    if (int rc = alloc(&c->d_hist[2], sizeof(uint32_t) * 256 * nblk)) return rc;
     if (int rc = alloc(&c->d_tot, sizeof(uint32_t) * 256)) return rc;
+    if (int rc = alloc(&c->d_bucket, sizeof(uint32_t) * kSortBucketWords)) return rc;
+    PGTI_HIP_TRY(hipMemsetAsync(c->d_bucket, 0, sizeof(uint32_t) * kSortBucketWords, ws));
     if (int rc = alloc(&c->d_share, sizeof(int32_t) * n)) return rc;
     c->series_bytes = elems * store_bytes;
     c->sort_blocks = nblk;
@@ -366,6 +368,12 @@ int pgti_create(pgti_ctx** out, int device) {
     pgti_ctx* c = new (std::nothrow) pgti_ctx();
     if (!c) return fail(PGTI_ERR_OOM, "host allocation failed");
     c->device = device;
+    // Test hook: a smaller limit sends buckets through the slow ordering path of the epoch sort.
+    c->bucket_sort_cap = kBucketSortKeys;
+    if (const char* v = getenv("PGTI_SORT_BUCKET_CAP")) {
+        const long cap = strtol(v, nullptr, 10);
+        if (cap >= 1 && cap < static_cast<long>(kBucketSortKeys)) c->bucket_sort_cap = static_cast<uint32_t>(cap);
+    }
     DeviceGuard guard(device);
     hipError_t e = guard.status;
     if (e == hipSuccess) e = hipStreamCreateWithFlags(&c->work_stream, hipStreamNonBlocking);

@@ -54,8 +54,10 @@ struct pgti_ctx {
     hipStream_t work_stream = nullptr;  // owns the sort and the load-time kernels
     uint64_t* d_keys[2] = {nullptr, nullptr};
     int32_t* d_vals[2] = {nullptr, nullptr};
-    uint32_t* d_hist[3] = {nullptr, nullptr, nullptr};  // per-(digit, tile) counts, rotating tables
-    uint32_t* d_tot = nullptr;                 // [256] digit totals of the current pass
+    uint32_t* d_hist[2] = {nullptr, nullptr};  // per-(digit, tile) counts of this pass / the next (radix path)
+    uint32_t* d_tot = nullptr;                 // [256] digit totals of the current pass (radix path)
+    uint32_t* d_bucket = nullptr;              // bucket path: totals, cursors, offsets (see kSortBucketWords)
+    uint32_t bucket_sort_cap = 0;              // largest bucket that is ordered in LDS
     int32_t* d_share = nullptr;                // this rank's starts, capacity n_windows
     uint32_t sort_blocks = 0;
     bool have_share = false;
@@ -103,9 +105,15 @@ hipError_t launch_reduce_rows(const double* row_acc, int64_t T, int32_t N, int32
                               double* out64, float* out32, hipStream_t s);
 
 // ---- epoch_sort.hip -------------------------------------------------------------------------
-constexpr uint32_t kSortTile = 2048;  // keys per workgroup per pass
-// One sorted order: n_keys keys key(seed, epoch, counter_base + i*counter_stride), 8 stable counting
-// passes; positions [out_lo, out_hi) of the sorted index list, plus value_offset, land in out[].
+constexpr uint32_t kSortTile = 2048;          // keys per workgroup per pass
+constexpr uint32_t kMaxSortBuckets = 1024;    // bucket path: buckets of the top key bits
+constexpr uint32_t kBucketSortKeys = 2048;    // bucket path: largest bucket ordered in LDS
+constexpr uint32_t kBucketPathKeys = 1u << 20;  // bucket path up to this many keys (average bucket <= 1024)
+// d_bucket: tot[kMaxSortBuckets], cursor[kMaxSortBuckets], off[kMaxSortBuckets + 1]; tot and cursor
+// must be zero when a sort starts (zeroed at allocation, and by the last kernel of every sort).
+constexpr uint32_t kSortBucketWords = 3 * kMaxSortBuckets + 1;
+// One sorted order: n_keys keys key(seed, epoch, counter_base + i*counter_stride) ordered by
+// (key, i); positions [out_lo, out_hi) of the sorted index list, plus value_offset, land in out[].
 // out may be c->d_vals[0] (free during the last pass) when the order is an intermediate result.
 struct SortPlan {
     uint32_t n_keys;

@@ -334,10 +334,12 @@ def test_identity_channel_returns_stored_bits():
 # ----------------------------------------------------------------------------------------------
 # index generation on its own
 # ----------------------------------------------------------------------------------------------
-@pytest.mark.parametrize("n", [1, 2, 3, 63, 64, 65, 1977, 2047, 2048, 2049, 3000, 4095, 4096, 4097, 10000, 105097, 500000, 524288, 524289, 1300003])
+@pytest.mark.parametrize("n", [1, 2, 3, 63, 64, 65, 1977, 2047, 2048, 2049, 3000, 4095, 4096, 4097, 6144, 10000, 105097, 500000, 524288, 524289,
+                               1048576, 1048577, 1300003])
 def test_epoch_order_sizes(n):
     # n spans one lane, one wave, the single-workgroup path up to 4096 keys (powers of two and ragged
-    # sizes), several tiles with a ragged tail, and more than 256 tiles
+    # sizes), the bucket path up to 2^20 keys with 16 to 1024 buckets, and the radix passes beyond
+    # (the per-digit scan over more than 256 tiles runs in several chunks with a carry)
     # (the per-digit scan over workgroups then runs in several chunks with a carry)
     P = Q = 1
     T = n + P + Q - 1
@@ -355,6 +357,28 @@ def test_epoch_order_sizes(n):
             ctx.epoch_indices(3, 1, r, world)
             pieces.append(ctx.get_indices())
         assert np.array_equal(np.concatenate(pieces), oracle.epoch_perm(3, 1, n))
+
+
+def test_epoch_order_with_oversized_buckets(monkeypatch):
+    # The bucket path orders a bucket in LDS up to a size limit and counts ranks the slow way above
+    # it.  Hash keys never fill a bucket that far, so the limit is lowered for this context: with 200
+    # about half of the buckets of n = 105,097 (512 buckets of about 205) take the slow way.
+    monkeypatch.setenv("PGTI_SORT_BUCKET_CAP", "200")
+    n, P, Q = 105097, 1, 1
+    series = np.zeros((n + P + Q - 1, 1, 1), np.float32)
+    with pgti.Context(0) as ctx:
+        ctx.load_series(series, P, Q, 4, pgti.PGTI_F32, [0.0], [1.0])
+        for seed, epoch in [(0, 0), (77, 5)]:
+            assert ctx.epoch_indices(seed, epoch) == n
+            assert np.array_equal(ctx.get_indices(), oracle.epoch_perm(seed, epoch, n))
+        ctx.epoch_indices(3, 1, 2, 5)
+        lo, hi = oracle.rank_share(n, 2, 5)
+        assert np.array_equal(ctx.get_indices(), oracle.epoch_perm(3, 1, n)[lo:hi])
+    monkeypatch.delenv("PGTI_SORT_BUCKET_CAP")
+    with pgti.Context(0) as ctx:  # and the limit is per context: back to the default here
+        ctx.load_series(series, P, Q, 4, pgti.PGTI_F32, [0.0], [1.0])
+        ctx.epoch_indices(0, 0)
+        assert np.array_equal(ctx.get_indices(), oracle.epoch_perm(0, 0, n))
 
 
 ORDERS = {"shuffle": 0, "sequential": 1, "batch_shuffle": 2}
