@@ -579,6 +579,47 @@ def test_more_streams_than_tracked_slots():
         torch.cuda.synchronize()
 
 
+def test_captured_batch_builds_replay_across_epochs():
+    # Per-batch builds captured into a HIP graph: after one eager build has made the stream wait for
+    # the share, further builds on it are plain kernel launches, and their arguments (the share
+    # buffer, the batch offsets, the outputs) do not change from epoch to epoch.  The same graph is
+    # replayed after every new index generation, with eager work and synchronisation in between,
+    # and every replay must give that epoch's batches.
+    w = workloads.WORKLOADS["tiny"]
+    series = workloads.make_series(w)
+    mean, std = oracle.series_stats(series)
+    s = torch.cuda.Stream()
+    with pgti.Context(0) as ctx:
+        ctx.load_series(series, w.P, w.Q, w.B, pgti.PGTI_F32, mean, std)
+        ctx.epoch_indices(4, 0)
+        nb = ctx.num_batches()
+        xs = [torch.zeros((w.B, w.P, w.N, w.F), device="cuda") for _ in range(nb)]
+        ys = [torch.zeros((w.B, w.Q, w.N, w.F), device="cuda") for _ in range(nb)]
+        ctx.build_batch(0, xs[0], ys[0], stream=s)
+        s.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=s):
+            for b in range(1, nb):
+                ctx.build_batch(b, xs[b], ys[b], stream=torch.cuda.current_stream())
+        for epoch in (0, 1, 2, 3):
+            if epoch:
+                ctx.epoch_indices(4, epoch)
+            for t in xs + ys:
+                t.zero_()
+            torch.cuda.synchronize()
+            with torch.cuda.stream(s):
+                ctx.build_batch(0, xs[0], ys[0], stream=s)  # eager: orders the stream behind the new share
+                graph.replay()
+            s.synchronize()
+            share = oracle.epoch_indices(4, epoch, 0, 1, w.n_windows)
+            for b in range(nb):
+                starts = share[b * w.B:(b + 1) * w.B]
+                wx, wy = oracle.build_batch(series, oracle.F32, w.P, w.Q, mean, std, starts)
+                assert _bits_equal(xs[b].cpu().numpy()[:len(starts)], wx), (epoch, b)
+                assert _bits_equal(ys[b].cpu().numpy()[:len(starts)], wy), (epoch, b)
+        del graph
+
+
 # ----------------------------------------------------------------------------------------------
 # several batches per launch
 # ----------------------------------------------------------------------------------------------
