@@ -207,7 +207,11 @@ int64_t pgti_num_batches(pgti_ctx* c);
  * aligned.  `stream` is a hipStream_t passed as void* (NULL = the default stream).  The kernel
  * is enqueued and the call returns without synchronising.  The stream must stay alive until the
  * next epoch-index generation, load or destroy call on this context has returned: those calls
- * order themselves behind the builds enqueued on it.
+ * order themselves behind the builds enqueued on it.  The first build on a stream after an index
+ * generation also makes that stream wait for the share (an event wait); every further build on it
+ * is kernel launches only and may be recorded into a HIP graph by stream capture.  Such a graph
+ * stays valid for later epochs of the same share length (its arguments do not change); replay it
+ * behind one ordinary build on the same stream, which supplies the wait.
  * Returns the number of valid samples B' in 1..B.  A short last batch is not padded: rows
  * j >= B' of the outputs are left untouched.
  * Errors: STATE, RANGE (batch_no outside [0, num_batches)), ARG (null or misaligned), HIP.
