@@ -190,28 +190,46 @@ __device__ __forceinline__ uint32_t bf16_bits(float v) {
     return (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;
 }
 
-// Output stores carry the non-temporal hint (written once, never re-read by these kernels) and
-// agent scope: on MI355X `sc1 nt` stores measured 3.5 % faster than `nt` alone for this
-// read-stream + write-stream mix (80.3 % vs 77.6 % of the HBM peak in the same harness), plain
-// stores 71 %.  The compiler's non-temporal builtin only sets `nt`, hence the two asm statements.
+// Output stores carry the non-temporal hint (written once, never re-read by these kernels).  With
+// fp32 storage they also carry agent scope: on MI355X `sc1 nt` stores measured 3.5 % faster than `nt`
+// alone for the 1:1 read-stream + write-stream mix (80.3 % vs 77.6 % of the HBM peak in the same
+// harness), plain stores 71 %; with bf16 storage (1:2 mix) `nt` alone measured 0.5 % faster.  The
+// compiler's non-temporal builtin only sets `nt`, hence the asm statements.
+template <bool AGENT_SCOPE>
 __device__ __forceinline__ void stream_store_16(void* dst, f32x4 v) {
-    asm volatile("global_store_dwordx4 %0, %1, off sc1 nt" ::"v"(dst), "v"(v) : "memory");
+    if constexpr (AGENT_SCOPE) asm volatile("global_store_dwordx4 %0, %1, off sc1 nt" ::"v"(dst), "v"(v) : "memory");
+    else asm volatile("global_store_dwordx4 %0, %1, off nt" ::"v"(dst), "v"(v) : "memory");
 }
 __device__ __forceinline__ void stream_store_8(void* dst, u32x2 v) {
     asm volatile("global_store_dwordx2 %0, %1, off sc1 nt" ::"v"(dst), "v"(v) : "memory");
 }
 
-// Stores output quad number `index` of the array at `base`: 16 bytes of fp32, or 8 bytes of bf16 when
-// the outputs are emitted in bf16.
+// Where output quad q of sample j goes: 16 bytes of fp32, or 8 bytes when the outputs are bf16.
+// Computed (and anchored in registers) before the loaded data is needed, so that the address
+// arithmetic runs while the load is in flight: a wave lives for one quad, and every instruction
+// between the arrival of its data and its store costs bandwidth (+2 points with bf16 storage).
 template <bool OUT_BF16>
-__device__ __forceinline__ void store_quad(void* base, size_t index, f32x4 r) {
+__device__ __forceinline__ void* quad_destination(const GatherArgs& a, uint32_t j, uint32_t q) {
+    constexpr size_t kBytes = OUT_BF16 ? 8 : 16;
+    const bool in_x = q < a.units_x;
+    char* base = static_cast<char*>(in_x ? a.out_x : a.out_y);
+    const size_t index = in_x ? static_cast<size_t>(j) * a.units_x + q
+                              : static_cast<size_t>(j) * (a.units_total - a.units_x) + (q - a.units_x);
+    void* dst = base + index * kBytes;
+    asm volatile("" ::"v"(dst));
+    return dst;
+}
+
+// Stores one standardised quad at dst: fp32, or bf16 (round to nearest even).
+template <bool OUT_BF16, bool AGENT_SCOPE>
+__device__ __forceinline__ void store_quad(void* dst, f32x4 r) {
     if constexpr (OUT_BF16) {
         u32x2 o;
         o.x = bf16_bits(r.x) | (bf16_bits(r.y) << 16);
         o.y = bf16_bits(r.z) | (bf16_bits(r.w) << 16);
-        stream_store_8(static_cast<u32x2*>(base) + index, o);
+        stream_store_8(dst, o);
     } else {
-        stream_store_16(static_cast<f32x4*>(base) + index, r);
+        stream_store_16<AGENT_SCOPE>(dst, r);
     }
 }
 
@@ -226,11 +244,8 @@ __global__ void __launch_bounds__(THREADS) gather_quads_kernel(GatherArgs a) {
     pin_uniform<FSTATIC>(t);
     if (q >= a.units_total) return;
     const f32x4 v = load_quad<STORE_BYTES, STREAM>(a.series, e0 + 4ll * q);
-    const f32x4 r = standardise_quad<FAST>(v, t);
-    if (q < a.units_x)
-        store_quad<OUT_BF16>(a.out_x, static_cast<size_t>(j) * a.units_x + q, r);
-    else
-        store_quad<OUT_BF16>(a.out_y, static_cast<size_t>(j) * (a.units_total - a.units_x) + (q - a.units_x), r);
+    void* dst = quad_destination<OUT_BF16>(a, j, q);
+    store_quad<OUT_BF16, STORE_BYTES == 4>(dst, standardise_quad<FAST>(v, t));
 }
 
 // Row-centric variant for batches of CONSECUTIVE starts (sequential and batch-level-shuffled
@@ -272,8 +287,10 @@ __global__ void __launch_bounds__(THREADS) gather_rows_kernel(RowArgs a) {
     for (uint32_t j = j_lo; j <= j_hi; ++j) {
         const uint32_t p = rr - j;  // step of sample j that shows this row
         const size_t sample = first_sample + j;
-        if (p < a.P) store_quad<OUT_BF16>(a.g.out_x, (sample * a.P + p) * a.row_quads + q, r);
-        else store_quad<OUT_BF16>(a.g.out_y, (sample * Q + (p - a.P)) * a.row_quads + q, r);
+        constexpr size_t kBytes = OUT_BF16 ? 8 : 16;
+        char* dst = (p < a.P) ? static_cast<char*>(a.g.out_x) + ((sample * a.P + p) * a.row_quads + q) * kBytes
+                              : static_cast<char*>(a.g.out_y) + ((sample * Q + (p - a.P)) * a.row_quads + q) * kBytes;
+        store_quad<OUT_BF16, true>(dst, r);
     }
 }
 
@@ -313,12 +330,9 @@ __global__ void __launch_bounds__(THREADS) gather_octs_kernel(GatherArgs a) {
     const QuadStats t = quad_stats<FSTATIC, FAST>(2 * o, a);
     pin_uniform<FSTATIC>(t);
     if (o >= a.units_total) return;
+    void* dst = quad_destination<false>(a, j, o);  // an oct of bf16 is 16 bytes, like a quad of fp32
     const u32x4 r = standardised_oct<FSTATIC, STREAM, FAST>(a.series, e0 + 8ll * o, o, t, a);
-    u32x4* dst = (o < a.units_x)
-                     ? static_cast<u32x4*>(a.out_x) + static_cast<size_t>(j) * a.units_x + o
-                     : static_cast<u32x4*>(a.out_y) + static_cast<size_t>(j) * (a.units_total - a.units_x) +
-                           (o - a.units_x);
-    stream_store_16(dst, __builtin_bit_cast(f32x4, r));
+    stream_store_16<true>(dst, __builtin_bit_cast(f32x4, r));
 }
 
 // Row kernel on octs: row_quads counts octs per row.
@@ -344,7 +358,7 @@ __global__ void __launch_bounds__(THREADS) gather_rows_octs_kernel(RowArgs a) {
         const size_t sample = first_sample + j;
         u32x4* dst = (p < a.P) ? static_cast<u32x4*>(a.g.out_x) + (sample * a.P + p) * a.row_quads + o
                                : static_cast<u32x4*>(a.g.out_y) + (sample * Q + (p - a.P)) * a.row_quads + o;
-        stream_store_16(dst, __builtin_bit_cast(f32x4, r));
+        stream_store_16<true>(dst, __builtin_bit_cast(f32x4, r));
     }
 }
 
