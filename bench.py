@@ -39,6 +39,8 @@ def parse_args():
     ap.add_argument("--out-dtype", default="f32", choices=["f32", "bf16"],
                     help="output element type (the headline metric uses fp32 outputs)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--repeats", type=int, default=5,
+                    help="further timed passes of the same steps, reported as median / max / min beside value")
     ap.add_argument("--cpu-batches", type=int, default=0, help="oracle batches on one core (0 = auto)")
     ap.add_argument("--roofline-launches", type=int, default=4096,
                     help="upper bound on back-to-back launches in the kernel-duration measurement")
@@ -249,6 +251,10 @@ def main():
 
     # ---- warm-up, timed region, kernel rate: k batches per launch, then one batch per launch -------
     snaps, elapsed = timed(k)
+    repeat_values = []
+    for _ in range(max(0, args.repeats)):
+        n_r, t_r = timed(k)
+        repeat_values.append(n_r / t_r)
     rate_k = kernel_rate(k)
     snaps1, elapsed1 = timed(1) if k > 1 else (snaps, elapsed)
     rate_1 = kernel_rate(1) if k > 1 else rate_k
@@ -303,6 +309,11 @@ def main():
             "roofline": {"achieved": rate_1["achieved"], "frac": rate_1["achieved"] / HBM_PEAK_GBS,
                          **{kk: v for kk, v in rate_1.items() if kk != "achieved"}},
         },
+        # the same K steps timed again (each pass with its own warm-up and synchronisation): run-to-run spread
+        "repeats": {"count": len(repeat_values), "unit": "snapshots/s",
+                    "median": float(sorted(repeat_values)[len(repeat_values) // 2]) if repeat_values else None,
+                    "min": min(repeat_values) if repeat_values else None,
+                    "max": max(repeat_values) if repeat_values else None},
         "epoch_indices_ms": t_idx * 1e3,
         "copy_calibration": {"count": args.copy_calibration, "bytes_read": xs[0][0].numel() * xs[0][0].element_size(),
                              "bytes_written": xs[0][0].numel() * xs[0][0].element_size()},
