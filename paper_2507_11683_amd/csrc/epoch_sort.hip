@@ -251,7 +251,7 @@ __global__ void __launch_bounds__(kSmallSortThreads) small_sort_kernel(uint64_t 
 }
 
 // ---- bucket path: count, scatter, one workgroup per bucket --------------------------------------
-// Bucket of a key = its top `dbits` bits, D = 2^dbits <= kMaxBuckets buckets.  tot[], cursor[] (D
+// Bucket of a key = its top `dbits` bits, D = 2^dbits <= kMaxSortBuckets buckets.  tot[], cursor[] (D
 // entries each) are zero between sorts: the last kernel clears what the first two filled.
 constexpr uint32_t kBucketBins = kMaxSortBuckets / kThreads;  // bins per thread in the offset scan: 4
 static_assert(kBucketBins * kThreads == kMaxSortBuckets, "whole bins per thread");
