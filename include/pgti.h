@@ -46,7 +46,10 @@ typedef enum {
     PGTI_ERR_HIP = -6    /* any other HIP runtime error (text in pgti_last_error) */
 } pgti_status;
 
-/* Creates a context on GPU `device` (ordinal as seen by HIP).  *out receives the handle. */
+/* Creates a context on GPU `device` (ordinal as seen by HIP).  *out receives the handle.
+ * Reads the environment variable PGTI_SORT_BUCKET_CAP once, here: a test hook that lowers the
+ * size (1..2047) up to which the epoch sort orders a bucket in on-chip memory, so that the slow
+ * ordering path for oversized buckets can be exercised; results do not depend on it. */
 int pgti_create(pgti_ctx** out, int device);
 
 /* Frees everything the context owns after waiting for the device work it enqueued on its own
