@@ -79,14 +79,31 @@ __global__ void __launch_bounds__(kThreads) row_sums_kernel(const float* __restr
     const double tod = synth ? static_cast<double>(time_of_day(row0 + row, period)) : 0.0;
     const double mu = mean64 ? mean64[f] : 0.0;
     double acc = 0.0;
-    for (int32_t node = lane; node < N; node += 64) {
-        double v = synth ? tod : static_cast<double>(p[static_cast<int64_t>(node) * F_src]);
+    auto add = [&](double v) {
         if (mean64) {
-            double d = v - mu;
+            const double d = v - mu;
             acc += d * d;
         } else {
             acc += v;
         }
+    };
+    if (synth) {
+        // same value for every node of the row; same additions, in the same order, as for a stored feature
+        for (int32_t node = lane; node < N; node += 64) add(tod);
+    } else {
+        // Sixteen loads are issued before the first is added (a wave has a whole row to itself, so
+        // its load latencies would otherwise run one after the other); the additions keep the node
+        // order.  The loads are unconditional inside this branch so that they can be in flight together.
+        constexpr int32_t kAhead = 16;
+        int32_t node = lane;
+        for (; node + 64 * (kAhead - 1) < N; node += 64 * kAhead) {
+            float v[kAhead];
+#pragma unroll
+            for (int32_t u = 0; u < kAhead; ++u) v[u] = p[static_cast<int64_t>(node + 64 * u) * F_src];
+#pragma unroll
+            for (int32_t u = 0; u < kAhead; ++u) add(static_cast<double>(v[u]));
+        }
+        for (; node < N; node += 64) add(static_cast<double>(p[static_cast<int64_t>(node) * F_src]));
     }
 #pragma unroll
     for (int off = 32; off >= 1; off >>= 1) acc += __shfl_xor(acc, off, 64);
