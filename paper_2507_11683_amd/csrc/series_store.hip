@@ -122,13 +122,27 @@ __global__ void __launch_bounds__(kThreads) reduce_rows_alg1_kernel(const double
     __shared__ double part[kThreads];
     const int64_t last_row = n_train + P - 1;  // rows [0, last_row) appear in x_train
     double acc = 0.0;
-    for (int64_t t = threadIdx.x; t < last_row; t += kThreads) {
+    auto row_total = [&](int64_t t) {
+        double total = 0.0;
+        for (int32_t f = 0; f < F; ++f) total += row_acc[t * F + f];
+        return total;
+    };
+    auto add_row = [&](int64_t t, double total) {
         const int64_t hi = t < n_train - 1 ? t : n_train - 1;
         const int64_t lo = t - P + 1 > 0 ? t - P + 1 : 0;
-        double row_total = 0.0;
-        for (int32_t f = 0; f < F; ++f) row_total += row_acc[t * F + f];
-        acc += static_cast<double>(hi - lo + 1) * row_total;
+        acc += static_cast<double>(hi - lo + 1) * total;
+    };
+    // rows are read eight ahead (one workgroup walks the whole table); the additions keep the row order
+    constexpr int kAhead = 8;
+    int64_t t = threadIdx.x;
+    for (; t + static_cast<int64_t>(kThreads) * (kAhead - 1) < last_row; t += static_cast<int64_t>(kThreads) * kAhead) {
+        double v[kAhead];
+#pragma unroll
+        for (int u = 0; u < kAhead; ++u) v[u] = row_total(t + static_cast<int64_t>(kThreads) * u);
+#pragma unroll
+        for (int u = 0; u < kAhead; ++u) add_row(t + static_cast<int64_t>(kThreads) * u, v[u]);
     }
+    for (; t < last_row; t += kThreads) add_row(t, row_total(t));
     part[threadIdx.x] = acc;
     __syncthreads();
     for (int off = kThreads / 2; off >= 1; off >>= 1) {
@@ -154,7 +168,17 @@ __global__ void __launch_bounds__(kThreads) reduce_rows_kernel(const double* __r
     __shared__ double part[kThreads];
     const int32_t f = blockIdx.x;
     double acc = 0.0;
-    for (int64_t t = threadIdx.x; t < T; t += kThreads) acc += row_acc[t * F + f];
+    // rows are read eight ahead (one workgroup walks a whole column); the additions keep the row order
+    constexpr int kAhead = 8;
+    int64_t t = threadIdx.x;
+    for (; t + static_cast<int64_t>(kThreads) * (kAhead - 1) < T; t += static_cast<int64_t>(kThreads) * kAhead) {
+        double v[kAhead];
+#pragma unroll
+        for (int u = 0; u < kAhead; ++u) v[u] = row_acc[(t + static_cast<int64_t>(kThreads) * u) * F + f];
+#pragma unroll
+        for (int u = 0; u < kAhead; ++u) acc += v[u];
+    }
+    for (; t < T; t += kThreads) acc += row_acc[t * F + f];
     part[threadIdx.x] = acc;
     __syncthreads();
     for (int off = kThreads / 2; off >= 1; off >>= 1) {
