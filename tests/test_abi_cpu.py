@@ -76,3 +76,12 @@ def test_product_package_does_not_import_the_oracle():
         if f.endswith((".py", ".c", ".h")):
             text = open(os.path.join(oracle_dir, f)).read()
             assert "paper_2507_11683_amd" not in text and "pgti.h" not in text, f
+
+
+def test_bench_refuses_more_than_one_gpu():
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
+    assert r.returncode != 0 and "one GPU" in (r.stdout + r.stderr)
+

@@ -575,3 +575,23 @@ def test_bf16_outputs_are_the_rounded_fp32_outputs():
         assert np.array_equal(got, lib)
         widened = (got.astype(np.uint32) << 16).view(np.float32)
         assert np.all(np.abs(widened - ref) <= np.abs(ref) * 2.0 ** -8)  # within half a bf16 ulp
+
+
+def test_build_batch_into_caller_buffers_is_the_same_call():
+    # `out=` only changes where the wrapper puts the result
+    rng = np.random.default_rng(5)
+    series = rng.normal(50, 10, (40, 5, 2)).astype(np.float32)
+    mean, std = np.array([1, 2], np.float32), np.array([3, 4], np.float32)
+    starts = [0, 5, 7]
+    fresh = oracle.build_batch(series, oracle.F32, 3, 2, mean, std, starts)
+    bx, by = np.full((4, 3, 5, 2), 7, np.float32), np.full(100, 7, np.float32)
+    into = oracle.build_batch(series, oracle.F32, 3, 2, mean, std, starts, out=(bx, by))
+    assert np.array_equal(fresh[0], into[0]) and np.array_equal(fresh[1], into[1])
+    assert np.shares_memory(into[0], bx) and np.shares_memory(into[1], by) and bx[3].min() == 7
+    fresh16 = oracle.build_batch_bf16_out(series, oracle.F32, 3, 2, mean, std, starts)
+    b16 = (np.zeros((3, 3, 5, 2), np.uint16), np.zeros((3, 2, 5, 2), np.uint16))
+    into16 = oracle.build_batch_bf16_out(series, oracle.F32, 3, 2, mean, std, starts, out=b16)
+    assert np.array_equal(fresh16[0], into16[0]) and np.array_equal(fresh16[1], into16[1])
+    with pytest.raises(ValueError):
+        oracle.build_batch(series, oracle.F32, 3, 2, mean, std, starts, out=(bx[:1], by))
+
