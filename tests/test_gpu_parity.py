@@ -219,6 +219,18 @@ def test_statewide_whole_epoch_every_batch(statewide_series, order_name, out_bf1
     assert _whole_epochs_every_batch(w, statewide_series, ORDERS[order_name], out_bf16, w.epochs) == 3285
 
 
+@pytest.mark.parametrize("out_bf16", [False, True], ids=["f32out", "bf16out"])
+@pytest.mark.parametrize("order_name", ["shuffle", "sequential", "batch_shuffle"])
+@pytest.mark.parametrize("name", ["tiny", "medium", "medium_wide"])
+def test_small_workloads_every_batch_every_order(name, order_name, out_bf16):
+    # the three cache-resident configurations: every batch of the epoch for each order and output type
+    # (rows of 414 and 650 elements do not start on 16-byte boundaries, so the consecutive-start orders
+    # run the span kernel here)
+    w = workloads.WORKLOADS[name]
+    nb = -(-w.n_windows // w.B)
+    assert _whole_epochs_every_batch(w, workloads.make_series(w), ORDERS[order_name], out_bf16, w.epochs) == nb
+
+
 def test_statewide_bf16_rank3of16_every_batch_three_epochs(statewide_series):
     # bf16 storage, rank 3 of 16: all 206 batches of each of the three epochs
     w = workloads.WORKLOADS["statewide_bf16_rank3of16"]
