@@ -138,7 +138,11 @@ __global__ void __launch_bounds__(kThreads) reduce_rows_alg1_kernel(const double
     for (; t + static_cast<int64_t>(kThreads) * (kAhead - 1) < last_row; t += static_cast<int64_t>(kThreads) * kAhead) {
         double v[kAhead];
 #pragma unroll
-        for (int u = 0; u < kAhead; ++u) v[u] = row_total(t + static_cast<int64_t>(kThreads) * u);
+        for (int u = 0; u < kAhead; ++u) v[u] = 0.0;
+        for (int32_t f = 0; f < F; ++f) {  // features in order for every row, eight rows' loads in flight
+#pragma unroll
+            for (int u = 0; u < kAhead; ++u) v[u] += row_acc[(t + static_cast<int64_t>(kThreads) * u) * F + f];
+        }
 #pragma unroll
         for (int u = 0; u < kAhead; ++u) add_row(t + static_cast<int64_t>(kThreads) * u, v[u]);
     }
