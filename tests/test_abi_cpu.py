@@ -85,3 +85,16 @@ def test_bench_refuses_more_than_one_gpu():
     r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
     assert r.returncode != 0 and "one GPU" in (r.stdout + r.stderr)
 
+
+@pytest.mark.parametrize("compiler,flags", [("gcc", ["-std=c99"]), ("g++", ["-std=c++11", "-x", "c++"])])
+def test_header_is_plain_c_and_cxx(tmp_path, compiler, flags):
+    # the boundary is usable from C99 and from C++ without HIP or torch headers
+    import subprocess
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    src = tmp_path / "use_header.c"
+    src.write_text('#include "pgti.h"\n'
+                   "int main(void) { pgti_load_spec s; pgti_epoch_spec e; (void)s; (void)e;\n"
+                   "  return pgti_create(0, 0) == PGTI_ERR_ARG ? 0 : 1; }\n")
+    subprocess.check_call([compiler, *flags, "-Wall", "-Wextra", "-Werror", "-pedantic",
+                           "-I", os.path.join(root, "include"), "-c", str(src), "-o", str(tmp_path / "use_header.o")])
+
