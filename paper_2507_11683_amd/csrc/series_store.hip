@@ -149,11 +149,11 @@ __global__ void __launch_bounds__(kThreads) reduce_rows_alg1_kernel(const double
     for (; t < last_row; t += kThreads) add_row(t, row_total(t));
     part[threadIdx.x] = acc;
     __syncthreads();
-    for (int off = kThreads / 2; off >= 1; off >>= 1) {
+    for (uint32_t off = kThreads / 2; off >= 1; off >>= 1) {
         if (threadIdx.x < off) part[threadIdx.x] += part[threadIdx.x + off];
         __syncthreads();
     }
-    if (threadIdx.x < F) {
+    if (static_cast<int32_t>(threadIdx.x) < F) {
         double r = part[0] / count;
         if (take_sqrt) r = sqrt(r);
         for (int32_t f = threadIdx.x; f < F; f += kThreads) {
@@ -185,7 +185,7 @@ __global__ void __launch_bounds__(kThreads) reduce_rows_kernel(const double* __r
     for (; t < T; t += kThreads) acc += row_acc[t * F + f];
     part[threadIdx.x] = acc;
     __syncthreads();
-    for (int off = kThreads / 2; off >= 1; off >>= 1) {
+    for (uint32_t off = kThreads / 2; off >= 1; off >>= 1) {
         if (threadIdx.x < off) part[threadIdx.x] += part[threadIdx.x + off];
         __syncthreads();
     }
