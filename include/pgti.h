@@ -139,8 +139,9 @@ int pgti_get_stats(pgti_ctx* c, float* mean_out, float* std_out);
  * the order is unique whatever sorting method produces it).  Rank `rank` of `world` owns order[lo, hi), lo = floor(rank*n/world),
  * hi = floor((rank+1)*n/world): no padding, no dropping.  *n_share (HOST, may be NULL)
  * receives hi - lo.  Same arguments give the same bits on every run.
- * Replaces the previous share.  Stream ordering is handled inside: the sort waits for batch
- * builds already enqueued through this context, and later batch builds wait for the sort.
+ * Replaces the previous share.  Stream ordering is handled inside: the new order is computed in a
+ * staging buffer, concurrently with batch builds already enqueued through this context; a short
+ * copy that publishes it waits for those builds, and later batch builds wait for that copy.
  * Does not block the host.
  * Errors: STATE (no series), RANGE (rank >= world, world == 0), HIP.
  */

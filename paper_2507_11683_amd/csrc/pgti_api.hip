@@ -49,6 +49,7 @@ void free_series(pgti_ctx* c) {
     drop(c->d_tot);
     drop(c->d_bucket);
     drop(c->d_share);
+    drop(c->d_share_next);
     c->loaded = false;
     c->have_share = false;
     c->series_bytes = 0;
@@ -186,6 +187,7 @@ int load_impl(pgti_ctx* c, const float* src, const pgti_load_spec* spec) {
     if (int rc = alloc(&c->d_bucket, sizeof(uint32_t) * kSortBucketWords)) return rc;
     PGTI_HIP_TRY(hipMemsetAsync(c->d_bucket, 0, sizeof(uint32_t) * kSortBucketWords, ws));
     if (int rc = alloc(&c->d_share, sizeof(int32_t) * n)) return rc;
+    if (int rc = alloc(&c->d_share_next, sizeof(int32_t) * n)) return rc;
     c->series_bytes = elems * store_bytes;
     c->sort_blocks = nblk;
 
@@ -480,21 +482,17 @@ int pgti_epoch_indices_ex(pgti_ctx* c, const pgti_epoch_spec* spec, int64_t* n_s
     const uint64_t hi = ((static_cast<uint64_t>(spec->rank) + 1) * n) / spec->world;
     const uint32_t len = static_cast<uint32_t>(hi - lo);
 
-    // The share buffer is about to be overwritten: order the sort behind every batch build that
-    // was enqueued through this context since the last sort.
-    for (int k = 0; k < c->n_tracked; ++k) {
-        PGTI_HIP_TRY(hipEventRecord(c->tracked[k].event, c->tracked[k].stream));
-        PGTI_HIP_TRY(hipStreamWaitEvent(c->work_stream, c->tracked[k].event, 0));
-    }
-    c->n_tracked = 0;
-
+    // The new order is computed into a staging buffer, so it may run while batch builds of the
+    // current epoch still read the share; only the short copy that publishes it (below) is ordered
+    // behind them.  The builds keep reading one fixed address from epoch to epoch.
     hipStream_t ws = c->work_stream;
+    int32_t* share_out = c->d_share_next;
     if (spec->order == PGTI_ORDER_SHUFFLE) {
-        SortPlan plan{static_cast<uint32_t>(n), 0, 1, c->d_share, static_cast<uint32_t>(lo),
+        SortPlan plan{static_cast<uint32_t>(n), 0, 1, share_out, static_cast<uint32_t>(lo),
                       static_cast<uint32_t>(hi), static_cast<int32_t>(first_start)};
         PGTI_HIP_TRY(launch_sorted_order(c, spec->seed, spec->epoch, plan, ws));
     } else if (spec->order == PGTI_ORDER_SEQUENTIAL) {
-        PGTI_HIP_TRY(launch_sequential_order(c->d_share, len, static_cast<int32_t>(first_start + lo), ws));
+        PGTI_HIP_TRY(launch_sequential_order(share_out, len, static_cast<int32_t>(first_start + lo), ws));
     } else {
         // Order of the full batches of the partition [lo, hi): keys on the position of each batch's
         // first element; the sorted batch numbers pass through d_vals[0], then expand to starts.
@@ -502,8 +500,17 @@ int pgti_epoch_indices_ex(pgti_ctx* c, const pgti_epoch_spec* spec, int64_t* n_s
         SortPlan plan{n_full, lo, static_cast<uint64_t>(c->B), c->d_vals[0], 0, n_full, 0};
         PGTI_HIP_TRY(launch_sorted_order(c, spec->seed, spec->epoch, plan, ws));
         PGTI_HIP_TRY(launch_expand_batches(c->d_vals[0], n_full, static_cast<uint32_t>(c->B),
-                                           static_cast<int32_t>(first_start + lo), c->d_share, len, ws));
+                                           static_cast<int32_t>(first_start + lo), share_out, len, ws));
     }
+    // Publish: the share is overwritten only after every batch build that was enqueued through this
+    // context since the last index generation has finished reading it.
+    for (int k = 0; k < c->n_tracked; ++k) {
+        PGTI_HIP_TRY(hipEventRecord(c->tracked[k].event, c->tracked[k].stream));
+        PGTI_HIP_TRY(hipStreamWaitEvent(ws, c->tracked[k].event, 0));
+    }
+    c->n_tracked = 0;
+    if (len > 0)
+        PGTI_HIP_TRY(hipMemcpyAsync(c->d_share, share_out, sizeof(int32_t) * len, hipMemcpyDeviceToDevice, ws));
     PGTI_HIP_TRY(hipEventRecord(c->ev_share_ready, ws));
     c->share_lo = static_cast<int64_t>(lo);
     c->share_hi = static_cast<int64_t>(hi);

@@ -58,7 +58,8 @@ struct pgti_ctx {
     uint32_t* d_tot = nullptr;                 // [256] digit totals of the current pass (radix path)
     uint32_t* d_bucket = nullptr;              // bucket path: totals, cursors, offsets (see kSortBucketWords)
     uint32_t bucket_sort_cap = 0;              // largest bucket that is ordered in LDS
-    int32_t* d_share = nullptr;                // this rank's starts, capacity n_windows
+    int32_t* d_share = nullptr;                // this rank's starts, capacity n_windows (what the builds read)
+    int32_t* d_share_next = nullptr;           // where the next order is computed while builds still read d_share
     uint32_t sort_blocks = 0;
     bool have_share = false;
     bool share_consecutive = false;  // batches hold consecutive starts (sequential / batch-shuffled order)

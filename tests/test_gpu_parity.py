@@ -565,6 +565,38 @@ def test_batches_follow_new_epoch_without_host_sync():
             assert _bits_equal(y[:len(last)].cpu().numpy(), wy)
 
 
+def test_next_sort_overlaps_running_builds():
+    # The next order is computed in a staging buffer while the builds of the current epoch still read
+    # the share; only the copy that publishes it waits for them.  Five epochs are enqueued back to back with no
+    # host synchronisation, each as one whole-epoch launch (0.25 ms of device work, so the following
+    # index generations are enqueued while it runs) into its own outputs, on alternating streams;
+    # every epoch's outputs must be that epoch's batches.
+    w = workloads.WORKLOADS["medium"]
+    series = workloads.make_series(w)
+    mean, std = oracle.series_stats(series)
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    epochs = range(5)
+    with pgti.Context(0) as ctx:
+        ctx.load_series(series, w.P, w.Q, w.B, pgti.PGTI_F32, mean, std)
+        ctx.epoch_indices(21, 0)
+        nb = ctx.num_batches()
+        outs = [(torch.zeros((nb, w.B, w.P, w.N, w.F), device="cuda"), torch.zeros((nb, w.B, w.Q, w.N, w.F), device="cuda"))
+                for _ in epochs]
+        torch.cuda.synchronize()
+        for e in epochs:
+            ctx.epoch_indices(21, e)
+            assert ctx.build_batches(0, nb, outs[e][0], outs[e][1], stream=streams[e % 2]) == w.n_windows
+        torch.cuda.synchronize()
+        for e in epochs:
+            share = oracle.epoch_indices(21, e, 0, 1, w.n_windows)
+            gx = outs[e][0].cpu().numpy().reshape(nb * w.B, w.P, w.N, w.F)
+            gy = outs[e][1].cpu().numpy().reshape(nb * w.B, w.Q, w.N, w.F)
+            for first in range(0, w.n_windows, 4096):
+                st = share[first:first + 4096]
+                wx, wy = oracle.build_batch(series, oracle.F32, w.P, w.Q, mean, std, st)
+                assert _bits_equal(gx[first:first + len(st)], wx) and _bits_equal(gy[first:first + len(st)], wy), (e, first)
+
+
 def test_more_streams_than_tracked_slots():
     # the context tracks 8 streams between two index generations; builds on 11 streams still order
     # correctly against the next sort and give the right batches
