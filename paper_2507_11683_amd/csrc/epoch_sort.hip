@@ -6,7 +6,7 @@
 // function.
 //
 // Three ways to get that order, by the number of keys n:
-//   n <= 4,096       one launch of one workgroup: keys are generated into LDS and ordered by
+//   n <= 1,024       one launch of one workgroup: keys are generated into LDS and ordered by
 //                    (key, index) with a bitonic network.
 //   n <= 1,048,576   (every benchmark workload) three launches: count the keys per bucket of the top
 //                    4..10 key bits; scatter every (key, index) into its bucket (place inside the
@@ -211,8 +211,8 @@ __global__ void __launch_bounds__(kThreads) scatter_kernel(
 // One workgroup orders up to kSmallSortKeys keys in LDS.  Slots n..m-1 (m = n rounded up to a power
 // of two) hold the largest key with their own slot number as index, which is above every real
 // index, so they end up behind the n real entries.
-constexpr uint32_t kSmallSortKeys = 4096;
-constexpr uint32_t kSmallSortThreads = 1024;
+constexpr uint32_t kSmallSortKeys = 1024;
+constexpr uint32_t kSmallSortThreads = 512;
 
 __global__ void __launch_bounds__(kSmallSortThreads) small_sort_kernel(uint64_t seed, uint64_t epoch, uint32_t n,
                                                                         uint32_t m, uint64_t counter_base,

@@ -346,10 +346,10 @@ def test_identity_channel_returns_stored_bits():
 # ----------------------------------------------------------------------------------------------
 # index generation on its own
 # ----------------------------------------------------------------------------------------------
-@pytest.mark.parametrize("n", [1, 2, 3, 63, 64, 65, 1977, 2047, 2048, 2049, 3000, 4095, 4096, 4097, 6144, 10000, 105097, 500000, 524288, 524289,
+@pytest.mark.parametrize("n", [1, 2, 3, 63, 64, 65, 700, 1023, 1024, 1025, 1977, 2047, 2048, 2049, 3000, 4095, 4096, 4097, 6144, 10000, 105097, 500000, 524288, 524289,
                                1048576, 1048577, 1300003])
 def test_epoch_order_sizes(n):
-    # n spans one lane, one wave, the single-workgroup path up to 4096 keys (powers of two and ragged
+    # n spans one lane, one wave, the single-workgroup path up to 1024 keys (powers of two and ragged
     # sizes), the bucket path up to 2^20 keys with 16 to 1024 buckets, and the radix passes beyond
     # (the per-digit scan over more than 256 tiles runs in several chunks with a carry)
     # (the per-digit scan over workgroups then runs in several chunks with a carry)
