@@ -352,7 +352,6 @@ def test_epoch_order_sizes(n):
     # n spans one lane, one wave, the single-workgroup path up to 1024 keys (powers of two and ragged
     # sizes), the bucket path up to 2^20 keys with 16 to 1024 buckets, and the radix passes beyond
     # (the per-digit scan over more than 256 tiles runs in several chunks with a carry)
-    # (the per-digit scan over workgroups then runs in several chunks with a carry)
     P = Q = 1
     T = n + P + Q - 1
     series = np.zeros((T, 1, 1), np.float32)
