@@ -98,3 +98,14 @@ def test_header_is_plain_c_and_cxx(tmp_path, compiler, flags):
     subprocess.check_call([compiler, *flags, "-Wall", "-Wextra", "-Werror", "-pedantic",
                            "-I", os.path.join(root, "include"), "-c", str(src), "-o", str(tmp_path / "use_header.o")])
 
+
+def test_no_device_is_a_clean_error_not_a_fallback():
+    # without a GPU the product path reports the HIP error; it never computes on the host
+    import torch
+    if torch.cuda.is_available():
+        pytest.skip("a GPU is present")
+    from paper_2507_11683_amd import pgti
+    with pytest.raises(pgti.PgtiError) as err:
+        pgti.Context(0)
+    assert err.value.status == pgti.PGTI_ERR_HIP and "device" in str(err.value)
+
