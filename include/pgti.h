@@ -190,6 +190,31 @@ typedef struct pgti_epoch_spec {
 
 int pgti_epoch_indices_ex(pgti_ctx* c, const pgti_epoch_spec* spec, int64_t* n_share);
 
+/*
+ * Epoch index generation for callers that cannot allocate device memory: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  (pgti_epoch_indices works in a
+ * workspace that pgti_load_series allocated and needs a context; this call needs neither.)
+ *
+ * Same order, same split and same bits as pgti_epoch_indices for a series with `n_windows` valid
+ * starts: the starts 0..n_windows-1 sorted by (key(seed, epoch, i), i), of which rank `rank` of
+ * `world` owns order[lo, hi).  The share is written to share_out (DEVICE, int32, caller-owned,
+ * room for `capacity` >= hi - lo entries) by kernels enqueued on `stream` (a hipStream_t as void*,
+ * NULL = the default stream) of GPU `device`; the call returns without synchronising.
+ * The sort works in a fixed array of 12.6 MB that is part of the library's device image (each GPU
+ * the library runs on holds one copy until the process ends); its address is resolved once per
+ * device, by pgti_create on that device or else by the first call.  The call makes no hipMalloc,
+ * hipFree or other allocating call.
+ * Limit: n_windows <= 1,048,576 (PGTI_STATIC_MAX_WINDOWS); more is PGTI_ERR_RANGE.
+ * Every call on one GPU shares that GPU's array: calls that overlap in time on one GPU (different
+ * streams, or threads) race and give undefined shares; calls on one stream are ordered and safe.
+ * Returns hi - lo, or a negative pgti_status: ARG (n_windows <= 0, null or misaligned share_out,
+ * capacity too small), RANGE (limit, rank >= world, world == 0), HIP.
+ */
+#define PGTI_STATIC_MAX_WINDOWS 1048576
+int64_t pgti_epoch_indices_static(int device, int64_t n_windows, uint64_t seed, uint64_t epoch,
+                                  uint32_t rank, uint32_t world, int32_t* share_out, int64_t capacity,
+                                  void* stream);
+
 /* Test hook: copies the current share to host_out (HOST, int32, room for `capacity` entries).
  * Blocks until the sort has finished.  Returns the share length, or ERR_ARG if it does not fit. */
 int64_t pgti_get_indices(pgti_ctx* c, int32_t* host_out, int64_t capacity);

@@ -28,6 +28,8 @@
 // range of starts, Sec. 3.1) is an iota; the batch-level shuffle of Sec. 5.4 (fixed partition,
 // batch order shuffled, batch contents fixed) sorts one key per full batch and expands the sorted
 // batch numbers into starts.
+#include <mutex>
+
 #include "pgti_internal.h"
 
 namespace pgti {
@@ -421,27 +423,29 @@ __global__ void __launch_bounds__(kThreads) expand_batches_kernel(const int32_t*
 
 namespace {
 
-void launch_pass(pgti_ctx* c, uint32_t pass, uint32_t n, uint32_t nblk, const SortPlan& plan, uint32_t* hist,
+void launch_pass(const SortWorkspace* c, uint32_t pass, uint32_t n, uint32_t nblk, const SortPlan& plan, uint32_t* hist,
                  uint32_t* hist_next, hipStream_t s) {
-    const uint64_t* kin = c->d_keys[pass & 1];
-    const int32_t* vin = c->d_vals[pass & 1];
-    uint64_t* kout = c->d_keys[(pass + 1) & 1];
-    int32_t* vout = c->d_vals[(pass + 1) & 1];
+    const uint64_t* kin = c->keys[pass & 1];
+    const int32_t* vin = c->vals[pass & 1];
+    uint64_t* kout = c->keys[(pass + 1) & 1];
+    int32_t* vout = c->vals[(pass + 1) & 1];
     const dim3 grid(nblk), block(kThreads);
     if (pass == 0)
-        hipLaunchKernelGGL((scatter_kernel<true, false>), grid, block, 0, s, kin, vin, kout, vout, hist, c->d_tot,
+        hipLaunchKernelGGL((scatter_kernel<true, false>), grid, block, 0, s, kin, vin, kout, vout, hist, c->tot,
                            hist_next, n, nblk, 8 * pass, plan.out, plan.out_lo, plan.out_hi, plan.value_offset);
     else if (pass < 7)
-        hipLaunchKernelGGL((scatter_kernel<false, false>), grid, block, 0, s, kin, vin, kout, vout, hist, c->d_tot,
+        hipLaunchKernelGGL((scatter_kernel<false, false>), grid, block, 0, s, kin, vin, kout, vout, hist, c->tot,
                            hist_next, n, nblk, 8 * pass, plan.out, plan.out_lo, plan.out_hi, plan.value_offset);
     else
-        hipLaunchKernelGGL((scatter_kernel<false, true>), grid, block, 0, s, kin, vin, kout, vout, hist, c->d_tot,
+        hipLaunchKernelGGL((scatter_kernel<false, true>), grid, block, 0, s, kin, vin, kout, vout, hist, c->tot,
                            hist_next, n, nblk, 8 * pass, plan.out, plan.out_lo, plan.out_hi, plan.value_offset);
 }
 
 }  // namespace
 
-hipError_t launch_sorted_order(pgti_ctx* c, uint64_t seed, uint64_t epoch, const SortPlan& plan, hipStream_t s) {
+hipError_t launch_sorted_order(const SortWorkspace& w, uint64_t seed, uint64_t epoch, const SortPlan& plan,
+                               hipStream_t s) {
+    const SortWorkspace* c = &w;
     const uint32_t n = plan.n_keys;
     if (n == 0) return hipSuccess;
     if (n <= kSmallSortKeys) {
@@ -458,23 +462,23 @@ hipError_t launch_sorted_order(pgti_ctx* c, uint64_t seed, uint64_t epoch, const
         uint32_t dbits = 4;
         while ((1u << dbits) < kMaxSortBuckets && (n >> dbits) > 384u) ++dbits;
         const uint32_t D = 1u << dbits;
-        uint32_t* tot = c->d_bucket;
-        uint32_t* cursor = c->d_bucket + kMaxSortBuckets;
-        uint32_t* off = c->d_bucket + 2 * kMaxSortBuckets;
+        uint32_t* tot = c->bucket;
+        uint32_t* cursor = c->bucket + kMaxSortBuckets;
+        uint32_t* off = c->bucket + 2 * kMaxSortBuckets;
         hipLaunchKernelGGL(bucket_count_kernel, dim3(nblk), dim3(kThreads), 0, s, seed, epoch, n, plan.counter_base,
                            plan.counter_stride, dbits, tot);
         hipLaunchKernelGGL(bucket_scatter_kernel, dim3(nblk), dim3(kThreads), 0, s, seed, epoch, n, plan.counter_base,
-                           plan.counter_stride, dbits, tot, cursor, off, c->d_keys[1], c->d_vals[1]);
-        hipLaunchKernelGGL(bucket_sort_kernel, dim3(D), dim3(kThreads), 0, s, c->d_keys[1], c->d_vals[1], off, tot,
+                           plan.counter_stride, dbits, tot, cursor, off, c->keys[1], c->vals[1]);
+        hipLaunchKernelGGL(bucket_sort_kernel, dim3(D), dim3(kThreads), 0, s, c->keys[1], c->vals[1], off, tot,
                            cursor, n, c->bucket_sort_cap, plan.out, plan.out_lo, plan.out_hi, plan.value_offset);
         return hipGetLastError();
     }
     hipLaunchKernelGGL(keygen_kernel, dim3(nblk), dim3(kThreads), 0, s, seed, epoch, n, nblk, plan.counter_base,
-                       plan.counter_stride, c->d_keys[0], c->d_hist[0]);
+                       plan.counter_stride, c->keys[0], c->hist[0]);
     for (uint32_t pass = 0; pass < 8; ++pass) {
-        uint32_t* hist = c->d_hist[pass & 1];
-        uint32_t* hist_next = c->d_hist[(pass + 1) & 1];
-        hipLaunchKernelGGL(scan_kernel, dim3(kRadix), dim3(kThreads), 0, s, hist, c->d_tot, hist_next, nblk);
+        uint32_t* hist = c->hist[pass & 1];
+        uint32_t* hist_next = c->hist[(pass + 1) & 1];
+        hipLaunchKernelGGL(scan_kernel, dim3(kRadix), dim3(kThreads), 0, s, hist, c->tot, hist_next, nblk);
         launch_pass(c, pass, n, nblk, plan, hist, hist_next, s);
     }
     return hipGetLastError();
@@ -495,3 +499,100 @@ hipError_t launch_expand_batches(const int32_t* order, uint32_t n_full, uint32_t
 }
 
 }  // namespace pgti
+
+// ---- the epoch order for callers that cannot allocate ---------------------------------------------
+// pgti_epoch_indices_static works in this file-scope array instead of a workspace from hipMalloc:
+// bucketed keys u64[kStaticSortKeys], bucketed indices i32[kStaticSortKeys], then the bucket totals,
+// cursors and offsets (kSortBucketWords words).  Every GPU the library runs on holds its own copy at
+// its own address until the process ends; the name below is only a host-side handle for
+// hipGetSymbolAddress, the kernels receive the resolved device pointer.
+namespace pgti {
+namespace {
+
+constexpr uint32_t kStaticSortKeys = kBucketPathKeys;  // 1,048,576 keys: the whole bucket path
+constexpr size_t kStaticKeysBytes = sizeof(uint64_t) * kStaticSortKeys;
+constexpr size_t kStaticValsBytes = sizeof(int32_t) * kStaticSortKeys;
+constexpr size_t kStaticBucketBytes = sizeof(uint32_t) * kSortBucketWords;
+constexpr size_t kStaticScratchBytes = kStaticKeysBytes + kStaticValsBytes + ((kStaticBucketBytes + 255) / 256) * 256;
+
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[kMaxDevices] = {};
+
+// Zeroes `words` 32-bit words (a kernel, not a memset node, so that a caller may capture the call
+// into a HIP graph).
+__global__ void __launch_bounds__(kThreads) zero_words_kernel(uint32_t* __restrict__ p, uint32_t words) {
+    const uint32_t i = blockIdx.x * kThreads + threadIdx.x;
+    if (i < words) p[i] = 0u;
+}
+
+}  // namespace
+
+hipError_t static_sort_scratch(int device, void** ptr) {
+    *ptr = nullptr;
+    if (device < 0 || device >= kMaxDevices) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[device]) {
+        void* p = nullptr;
+        const hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));  // of the current device
+        if (e != hipSuccess) return e;
+        if (!p) return hipErrorInvalidSymbol;
+        g_scratch_ptr[device] = p;
+    }
+    *ptr = g_scratch_ptr[device];
+    return hipSuccess;
+}
+
+}  // namespace pgti
+
+extern "C" int64_t pgti_epoch_indices_static(int device, int64_t n_windows, uint64_t seed, uint64_t epoch,
+                                              uint32_t rank, uint32_t world, int32_t* share_out, int64_t capacity,
+                                              void* stream) {
+    using namespace pgti;
+    clear_error();
+    if (n_windows <= 0) return fail(PGTI_ERR_ARG, "n_windows must be positive (got %lld)", (long long)n_windows);
+    if (n_windows > static_cast<int64_t>(kStaticSortKeys))
+        return fail(PGTI_ERR_RANGE, "%lld windows exceed the %u this allocation-free call is built for",
+                    (long long)n_windows, kStaticSortKeys);
+    if (world == 0) return fail(PGTI_ERR_RANGE, "world must be at least 1");
+    if (rank >= world) return fail(PGTI_ERR_RANGE, "rank %u not in [0, %u)", rank, world);
+    const uint64_t n = static_cast<uint64_t>(n_windows);
+    const uint64_t lo = (static_cast<uint64_t>(rank) * n) / world, hi = ((static_cast<uint64_t>(rank) + 1) * n) / world;
+    const int64_t len = static_cast<int64_t>(hi - lo);
+    if (len > 0 && !share_out) return fail(PGTI_ERR_ARG, "null output pointer");
+    if (capacity < len)
+        return fail(PGTI_ERR_ARG, "share of %lld starts does not fit capacity %lld", (long long)len, (long long)capacity);
+    if (reinterpret_cast<uintptr_t>(share_out) & 3u) return fail(PGTI_ERR_ARG, "share_out must be 4-byte aligned");
+    if (len == 0) return 0;
+
+    int prev = -1;
+    PGTI_HIP_TRY(hipGetDevice(&prev));
+    if (prev != device) PGTI_HIP_TRY(hipSetDevice(device));
+    struct Restore {
+        int prev, device;
+        ~Restore() {
+            if (prev != device) (void)hipSetDevice(prev);
+        }
+    } restore{prev, device};
+
+    void* base = nullptr;
+    PGTI_HIP_TRY(static_sort_scratch(device, &base));
+    unsigned char* p = static_cast<unsigned char*>(base);
+    SortWorkspace w{};
+    w.keys[1] = reinterpret_cast<uint64_t*>(p);
+    w.vals[1] = reinterpret_cast<int32_t*>(p + kStaticKeysBytes);
+    w.bucket = reinterpret_cast<uint32_t*>(p + kStaticKeysBytes + kStaticValsBytes);
+    w.bucket_sort_cap = kBucketSortKeys;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    // The array keeps whatever the last call left (also a call that was cut short): totals and
+    // cursors must start at zero.
+    if (n > kSmallSortKeys)
+        hipLaunchKernelGGL(zero_words_kernel, dim3((2 * kMaxSortBuckets + kThreads - 1) / kThreads), dim3(kThreads), 0,
+                           s, w.bucket, 2 * kMaxSortBuckets);
+    const SortPlan plan{static_cast<uint32_t>(n), 0, 1, share_out, static_cast<uint32_t>(lo),
+                        static_cast<uint32_t>(hi), 0};
+    PGTI_HIP_TRY(launch_sorted_order(w, seed, epoch, plan, s));
+    return len;
+}

@@ -99,6 +99,11 @@ int check_geometry(int64_t T, int32_t N, int32_t F, int32_t P, int32_t Q, int32_
     return PGTI_OK;
 }
 
+SortWorkspace workspace_of(const pgti_ctx* c) {
+    return SortWorkspace{{c->d_keys[0], c->d_keys[1]}, {c->d_vals[0], c->d_vals[1]}, {c->d_hist[0], c->d_hist[1]},
+                         c->d_tot, c->d_bucket, c->bucket_sort_cap};
+}
+
 int check_stats(const float* mean, const float* stdev, int32_t F) {
     for (int32_t f = 0; f < F; ++f) {
         if (!std::isfinite(mean[f]) || !std::isfinite(stdev[f]))
@@ -354,6 +359,8 @@ int fail_hip(hipError_t e, const char* what) {
     return e == hipErrorOutOfMemory ? PGTI_ERR_OOM : PGTI_ERR_HIP;
 }
 
+void clear_error() { g_error[0] = 0; }
+
 }  // namespace pgti
 
 using namespace pgti;
@@ -378,6 +385,10 @@ int pgti_create(pgti_ctx** out, int device) {
     }
     DeviceGuard guard(device);
     hipError_t e = guard.status;
+    // Set-up of the allocation-free epoch order: resolve this device's copy of its scratch array now,
+    // so that the call itself never has to (it may run where symbol look-ups are unwelcome).
+    void* static_scratch = nullptr;
+    if (e == hipSuccess) e = static_sort_scratch(device, &static_scratch);
     if (e == hipSuccess) e = hipStreamCreateWithFlags(&c->work_stream, hipStreamNonBlocking);
     if (e == hipSuccess) e = hipEventCreateWithFlags(&c->ev_share_ready, hipEventDisableTiming);
     for (int k = 0; k < kMaxTrackedStreams && e == hipSuccess; ++k) {
@@ -490,7 +501,7 @@ int pgti_epoch_indices_ex(pgti_ctx* c, const pgti_epoch_spec* spec, int64_t* n_s
     if (spec->order == PGTI_ORDER_SHUFFLE) {
         SortPlan plan{static_cast<uint32_t>(n), 0, 1, share_out, static_cast<uint32_t>(lo),
                       static_cast<uint32_t>(hi), static_cast<int32_t>(first_start)};
-        PGTI_HIP_TRY(launch_sorted_order(c, spec->seed, spec->epoch, plan, ws));
+        PGTI_HIP_TRY(launch_sorted_order(workspace_of(c), spec->seed, spec->epoch, plan, ws));
     } else if (spec->order == PGTI_ORDER_SEQUENTIAL) {
         PGTI_HIP_TRY(launch_sequential_order(share_out, len, static_cast<int32_t>(first_start + lo), ws));
     } else {
@@ -498,7 +509,7 @@ int pgti_epoch_indices_ex(pgti_ctx* c, const pgti_epoch_spec* spec, int64_t* n_s
         // first element; the sorted batch numbers pass through d_vals[0], then expand to starts.
         const uint32_t n_full = len / static_cast<uint32_t>(c->B);
         SortPlan plan{n_full, lo, static_cast<uint64_t>(c->B), c->d_vals[0], 0, n_full, 0};
-        PGTI_HIP_TRY(launch_sorted_order(c, spec->seed, spec->epoch, plan, ws));
+        PGTI_HIP_TRY(launch_sorted_order(workspace_of(c), spec->seed, spec->epoch, plan, ws));
         PGTI_HIP_TRY(launch_expand_batches(c->d_vals[0], n_full, static_cast<uint32_t>(c->B),
                                            static_cast<int32_t>(first_start + lo), share_out, len, ws));
     }

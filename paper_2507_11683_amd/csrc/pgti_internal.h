@@ -75,6 +75,7 @@ namespace pgti {
 // ---- error plumbing (pgti_api.hip) ----------------------------------------------------------
 int fail(int status, const char* fmt, ...);
 int fail_hip(hipError_t e, const char* what);
+void clear_error();
 
 #define PGTI_HIP_TRY(expr)                                   \
     do {                                                     \
@@ -123,7 +124,21 @@ struct SortPlan {
     uint32_t out_lo, out_hi;
     int32_t value_offset;
 };
-hipError_t launch_sorted_order(pgti_ctx* c, uint64_t seed, uint64_t epoch, const SortPlan& plan, hipStream_t s);
+// Device memory a sort works in.  The bucket path (n_keys <= kBucketPathKeys) touches only keys[1],
+// vals[1] and bucket; the single-workgroup path (n_keys <= 1,024) touches none of it.
+struct SortWorkspace {
+    uint64_t* keys[2];
+    int32_t* vals[2];
+    uint32_t* hist[2];        // per-(digit, tile) counts of this pass / the next (radix path)
+    uint32_t* tot;            // [256] digit totals of the current pass (radix path)
+    uint32_t* bucket;         // kSortBucketWords words (bucket path)
+    uint32_t bucket_sort_cap; // largest bucket that is ordered in LDS
+};
+hipError_t launch_sorted_order(const SortWorkspace& w, uint64_t seed, uint64_t epoch, const SortPlan& plan,
+                               hipStream_t s);
+// The per-device address of the file-scope scratch array behind pgti_epoch_indices_static; resolves
+// it on the first call for `device`, which must be the current device.  No allocation.
+hipError_t static_sort_scratch(int device, void** ptr);
 hipError_t launch_sequential_order(int32_t* share, uint32_t len, int32_t first, hipStream_t s);
 hipError_t launch_expand_batches(const int32_t* order, uint32_t n_full, uint32_t B, int32_t base, int32_t* share,
                                  uint32_t len, hipStream_t s);

@@ -32,6 +32,7 @@ SIGNATURES = {
     "pgti_load_series_device": (ctypes.c_int, [_vp, _vp, _i64, _i32, _i32, _i32, _i32, _i32, ctypes.c_int, _vp, _vp]),
     "pgti_get_stats": (ctypes.c_int, [_vp, _vp, _vp]),
     "pgti_epoch_indices": (ctypes.c_int, [_vp, _u64, _u64, _u32, _u32, ctypes.POINTER(_i64)]),
+    "pgti_epoch_indices_static": (_i64, [ctypes.c_int, _i64, _u64, _u64, _u32, _u32, _vp, _i64, _vp]),
     "pgti_get_indices": (_i64, [_vp, _vp, _i64]),
     "pgti_num_batches": (_i64, [_vp]),
     "pgti_build_batch": (ctypes.c_int, [_vp, _i64, _vp, _vp, _vp]),
@@ -266,6 +267,20 @@ class Context:
     def build_batch_raw(self, batch_no: int, x_ptr: int, y_ptr: int, stream_handle: int) -> int:
         """Same call with raw device addresses (no per-call tensor checks): for timed loops."""
         return self._lib.pgti_build_batch(self._h, batch_no, x_ptr, y_ptr, stream_handle)
+
+
+PGTI_STATIC_MAX_WINDOWS = 1 << 20
+
+
+def epoch_indices_static(n_windows: int, seed: int, epoch: int, rank: int, world: int,
+                         share_out: torch.Tensor, stream=None, device: int = 0) -> int:
+    """pgti_epoch_indices_static: the share of (seed, epoch, rank, world) over n_windows starts into the
+    caller's int32 CUDA tensor, with no allocation anywhere in the call.  Returns the share length."""
+    if not (share_out.is_cuda and share_out.dtype == torch.int32 and share_out.is_contiguous()):
+        raise PgtiError(PGTI_ERR_ARG, "share_out must be a contiguous int32 CUDA tensor")
+    return _check(load_library().pgti_epoch_indices_static(device, n_windows, seed, epoch, rank, world,
+                                                           share_out.data_ptr(), share_out.numel(),
+                                                           _stream_handle(stream)))
 
 
 def last_error() -> str:
