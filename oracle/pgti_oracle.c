@@ -310,10 +310,11 @@ int oracle_build_batch_bf16_out(const void* series, int storage, int64_t T, int6
 }
 
 /* ------------------------------------------------------------------------------------------
- * Algorithm 1, the standard preprocessing, written as the paper lists it: visit every window,
- * append its x and its y (the slice one input length ahead), stack, then standardise both
- * stacks.  Memory grows as Eq. 1, so this is for tiny inputs: it is the brute-force
- * definition that index-batching must reproduce sample for sample.
+ * What Algorithm 1 (the standard preprocessing) materialises: for every window w the block
+ * x_all[w] = data[w .. w+P) and the block y_all[w] = data[w+P .. w+P+Q), the slice one input
+ * length ahead, all blocks stacked and every element standardised.  Memory grows as Eq. 1, so
+ * this is for tiny inputs: it is the brute-force definition that index-batching must reproduce
+ * sample for sample.
  * x_all is [n, P, N, F], y_all is [n, Q, N, F].
  * ---------------------------------------------------------------------------------------- */
 int oracle_alg1_preprocess(const float* data, int64_t T, int64_t N, int64_t F, int64_t P,

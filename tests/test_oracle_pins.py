@@ -173,23 +173,30 @@ def test_index_batching_equals_algorithm1(T, N, F, P, Q):
         assert np.array_equal(y_all[0, 0], x_all[P, 0])
 
 
-def test_alg1_against_plain_numpy_loop():
-    # Algorithm 1 written the way its listing reads, with numpy doing the arithmetic in fp32.
+def test_alg1_stacks_are_the_standardised_sliding_windows():
+    # What Algorithm 1 materialises, stated as a property instead of a procedure: element
+    # [w, p, node, f] of the stacked x is the standardised source value at time w + p, and of the
+    # stacked y the one at time w + P + p.  numpy builds all windows at once as a strided view and
+    # does the arithmetic in fp32 (one rounding per operation).
     rng = np.random.default_rng(5)
-    T, N, F, h = 30, 4, 2, 4
+    T, N, F, P, Q = 30, 4, 2, 4, 3
     data = (rng.standard_normal((T, N, F)) * 9 + 60).astype(np.float32)
     mean = np.array([59.5, 0.25], np.float32)
     std = np.array([9.25, 0.75], np.float32)
-    xs, ys = [], []
-    for w in range(T - (2 * h - 1)):
-        xs.append(data[w:w + h])
-        ys.append(data[w + h:w + 2 * h])
-    xs, ys = np.stack(xs, axis=0), np.stack(ys, axis=0)
-    xs, ys = (xs - mean) / std, (ys - mean) / std  # numpy fp32: one rounding per operation
-    x_all, y_all = oracle.alg1_preprocess(data, h, h, mean, std)
-    assert xs.dtype == np.float32
-    assert np.array_equal(x_all.view(np.uint32), xs.view(np.uint32))
-    assert np.array_equal(y_all.view(np.uint32), ys.view(np.uint32))
+    z = (data - mean) / std
+    assert z.dtype == np.float32
+    n = T - (P + Q) + 1
+    x_all, y_all = oracle.alg1_preprocess(data, P, Q, mean, std)
+    win = np.lib.stride_tricks.sliding_window_view(z, P + Q, axis=0)  # [n, N, F, P+Q]
+    assert win.shape[0] == n
+    win = np.moveaxis(win, -1, 1)                                     # [n, P+Q, N, F]
+    assert np.array_equal(x_all.view(np.uint32), np.ascontiguousarray(win[:, :P]).view(np.uint32))
+    assert np.array_equal(y_all.view(np.uint32), np.ascontiguousarray(win[:, P:]).view(np.uint32))
+    # spot elements through the scalar definition
+    for w, p, node, f in [(0, 0, 0, 0), (n - 1, P - 1, N - 1, F - 1), (7, 2, 1, 1), (n - 1, 0, 3, 0)]:
+        assert x_all[w, p, node, f] == np.float32(oracle.standardize(data[w + p, node, f], mean[f], std[f]))
+    for w, q, node, f in [(0, 0, 0, 0), (n - 1, Q - 1, N - 1, F - 1), (5, 1, 2, 1)]:
+        assert y_all[w, q, node, f] == np.float32(oracle.standardize(data[w + P + q, node, f], mean[f], std[f]))
 
 
 def test_start_out_of_range_is_rejected():
