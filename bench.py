@@ -1,19 +1,25 @@
 #!/usr/bin/env python3
 """Throughput of index-batched snapshot construction on one MI355X.
 
-A "step" is one pass of the hot path over one batch: the fused gather+standardise launch
-(pgti_build_batch); at every epoch boundary inside the timed region the epoch's shuffled index
-list is generated first (pgti_epoch_indices), so the timed region holds all per-epoch and
-per-batch work.  The resident series is loaded before timing starts (it is loaded once per run).
+A "step" is one pass of the hot path over one batch: the fused gather+standardise of one batch of
+the current epoch (pgti_build_batch / one slot of a pgti_build_batches launch).  The per-epoch part
+of the path, the shuffled index list (pgti_epoch_indices), is generated once per epoch as a training
+loop does it: before the first batch of an epoch, also when that boundary falls inside the timed
+steps.  The resident series is loaded before timing starts (it is loaded once per run).
 
-Prints ONE JSON line: whole-job snapshots/s, the roofline of the dominant kernel (measured live
-with HIP events on the launch stream) and the CPU oracle timed on this host as a baseline.
+`value` times exactly --steps batches in that steady state.  Beside it, in the same JSON line:
+`full_epoch` (one whole epoch, with and without its index generation), `one_batch_per_launch`
+(pgti_build_batch one call per batch: one caller stream, and two alternating caller streams),
+`other_workloads` (the remaining benchmark configurations, one timed pass each), `roofline` (the
+dominant kernel's average launch duration from HIP events on the launch stream) and `cpu_baseline`
+(the CPU oracle on this host).
 """
 from __future__ import annotations
 
 import argparse
 import json
 import os
+import re
 import sys
 import time
 
@@ -22,23 +28,26 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0  # MI355X HBM3E published peak
+ORDERS = ("shuffle", "sequential", "batch_shuffle")
 
 
 def parse_args():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=0, help="batches to time (0 = one full epoch)")
+    ap.add_argument("--steps", type=int, default=0, help="batches to time (0 = the workload's epochs)")
     ap.add_argument("--warmup", type=int, default=64)
     ap.add_argument("--workload", default="statewide")
     ap.add_argument("--batches-per-launch", type=int, default=0,
                     help="batches built by one launch (0 = auto: about 512 MB of traffic per launch)")
     ap.add_argument("--out-pairs", type=int, default=0,
                     help="output buffer sets rotated (0 = enough to exceed the 256 MB last-level cache)")
-    ap.add_argument("--order", default="shuffle", choices=["shuffle", "sequential", "batch_shuffle"],
+    ap.add_argument("--order", default="shuffle", choices=list(ORDERS),
                     help="epoch order (the headline metric is the global shuffle)")
     ap.add_argument("--out-dtype", default="f32", choices=["f32", "bf16"],
                     help="output element type (the headline metric uses fp32 outputs)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-other-workloads", action="store_true",
+                    help="skip the timed passes of the other benchmark configurations")
     ap.add_argument("--repeats", type=int, default=5,
                     help="further timed passes of the same steps, reported as median / max / min beside value")
     ap.add_argument("--cpu-batches", type=int, default=0, help="oracle batches on one core (0 = auto)")
@@ -50,29 +59,44 @@ def parse_args():
     return ap.parse_args()
 
 
-def traffic_from_profiles(workload: str, batches_per_launch: int):
-    """HBM bytes per launch measured with rocprofv3 --pmc (FETCH_SIZE / WRITE_SIZE, scaled by a
-    copy kernel of known size); recorded in profiles/ after a counter run of this same launch
-    shape, else null."""
-    path = os.path.join(ROOT, "profiles", f"gather_{workload}_pmc.md")
+def gather_kernel_name(w, order: str, out_dtype: str) -> str:
+    """The kernel pgti_build_batch(es) launches for this geometry, order and output type (the
+    selection rule of the library's launcher, restated)."""
+    R = w.N * w.F
+    ex, et = w.P * R, (w.P + w.Q) * R
+    both_bf16 = w.storage == "bf16" and out_dtype == "bf16"
+    if order != "shuffle" and R % 4 == 0:
+        return "gather_rows_octs_kernel" if both_bf16 and R % 8 == 0 else "gather_rows_kernel"
+    if ex % 4 == 0 and et % 4 == 0:
+        return "gather_octs_kernel" if both_bf16 and ex % 8 == 0 and et % 8 == 0 else "gather_quads_kernel"
+    return "gather_scalar_kernel"
+
+
+def traffic_from_profiles(workload: str, order: str, out_dtype: str, batches_per_launch: int, kernel: str):
+    """HBM bytes per launch measured with rocprofv3 --pmc (FETCH_SIZE / WRITE_SIZE, scaled by a copy
+    kernel of known size).  Counters cannot be read inside this process, so the figure comes from the
+    committed summary of a counter run of this same command, and only when that summary names the same
+    workload, order, output type, launch shape and kernel; else null."""
+    suffix = "" if (order, out_dtype) == ("shuffle", "f32") else f"_{order}_{out_dtype}"
+    rel = os.path.join("profiles", f"gather_{workload}{suffix}_pmc.md")
     try:
         found = {}
-        for line in open(path):
-            for key in ("traffic_bytes_per_launch", "batches_per_launch"):
-                if line.startswith(key + ":"):
-                    found[key] = float(line.split(":", 1)[1].split()[0])
-        if found.get("batches_per_launch", 1) == batches_per_launch:
-            return found.get("traffic_bytes_per_launch")
-    except OSError:
+        for line in open(os.path.join(ROOT, rel)):
+            m = re.match(r"^(traffic_bytes_per_launch|batches_per_launch|order|out_dtype|kernel|recorded):\s*(\S+)", line)
+            if m:
+                found[m.group(1)] = m.group(2)
+        if (int(float(found.get("batches_per_launch", -1))) == batches_per_launch
+                and found.get("order", "shuffle") == order and found.get("out_dtype", "f32") == out_dtype
+                and found.get("kernel", kernel) == kernel and "traffic_bytes_per_launch" in found):
+            return float(found["traffic_bytes_per_launch"]), f"{rel} (recorded {found.get('recorded', 'n/a')})"
+    except (OSError, ValueError):
         pass
-    return None
+    return None, None
 
 
 def cpu_baseline(w, series, mean, std, n_batches_1core: int, order: int = 0):
     """The oracle as it stands, on this host, on a bounded sample of the same workload."""
     import concurrent.futures as cf
-
-    import numpy as np
 
     import oracle
 
@@ -86,7 +110,7 @@ def cpu_baseline(w, series, mean, std, n_batches_1core: int, order: int = 0):
         t0 = time.perf_counter()
         per_batch(1 % nb)
         one = time.perf_counter() - t0
-        n_batches_1core = max(4, min(nb, int(12.0 / max(one, 1e-6))))
+        n_batches_1core = max(4, min(nb, int(10.0 / max(one, 1e-6))))
     picks = [int(i * nb / n_batches_1core) for i in range(n_batches_1core)]
     snaps = sum(min(w.B, len(share) - b * w.B) for b in picks)
     t0 = time.perf_counter()
@@ -114,6 +138,194 @@ def cpu_baseline(w, series, mean, std, n_batches_1core: int, order: int = 0):
     }
 
 
+class Runner:
+    """Timed passes of one loaded workload: builds on torch's current stream (and one side stream for
+    the two-stream leg), rotating output buffers so that writes cannot live in the last-level cache."""
+
+    def __init__(self, ctx, w, order: str, out_dtype: str, side_stream, k_req: int = 0, sets_req: int = 0):
+        import torch
+        from paper_2507_11683_amd import pgti
+        self.torch, self.pgti, self.ctx, self.w, self.order, self.out_dtype = torch, pgti, ctx, w, order, out_dtype
+        self.order_code = {"shuffle": pgti.PGTI_ORDER_SHUFFLE, "sequential": pgti.PGTI_ORDER_SEQUENTIAL,
+                           "batch_shuffle": pgti.PGTI_ORDER_BATCH_SHUFFLE}[order]
+        self.n_share = self.gen_indices(w.epochs[0])
+        self.nb = ctx.num_batches()
+        self.out_elem = 4 if out_dtype == "f32" else 2
+        out_torch = torch.float32 if out_dtype == "f32" else torch.bfloat16
+        self.bps = w.bytes_per_snapshot(self.out_elem)       # algorithmic bytes per snapshot
+        batch_bytes = w.B * self.bps                         # algorithmic read + write of a full batch
+        out_bytes = w.B * (w.P + w.Q) * w.N * w.F * self.out_elem
+        self.build_raw = ctx.build_batches_raw if out_dtype == "f32" else ctx.build_batches_bf16_raw
+        k = k_req or max(1, min(self.nb, -(-(512 << 20) // batch_bytes)))
+        if not k_req and order != "shuffle" and w.series_bytes_f32 > (256 << 20):
+            k = 1  # consecutive starts, write-bound row-centric kernel: measured fastest at one batch per launch
+        self.k = min(k, self.nb, 65535 // w.B)
+        self.sets = sets_req or min(64, max(3, -(-(768 << 20) // (self.k * out_bytes))))
+        k = self.k
+        self.xs = [torch.empty((k, w.B, w.P, w.N, w.F), dtype=out_torch, device="cuda") for _ in range(self.sets)]
+        self.ys = [torch.empty((k, w.B, w.Q, w.N, w.F), dtype=out_torch, device="cuda") for _ in range(self.sets)]
+        self.xp, self.yp = [t.data_ptr() for t in self.xs], [t.data_ptr() for t in self.ys]
+        self.xb = w.B * w.P * w.N * w.F * self.out_elem
+        self.yb = w.B * w.Q * w.N * w.F * self.out_elem
+        self.stream = torch.cuda.current_stream()
+        # one side stream for the whole process: streams share the few hardware queues of the device in
+        # creation order, and two streams on one queue cannot overlap
+        self.side = side_stream
+        self.kernel = gather_kernel_name(w, order, out_dtype)
+
+    def gen_indices(self, epoch: int) -> int:
+        w = self.w
+        return self.ctx.epoch_indices_ex(self.order_code, seed=w.seed, epoch=epoch, rank=w.rank, world=w.world)
+
+    def out_ptrs(self, launch: int, per_launch: int):
+        """Rotates launches over every slot of every set (per_launch consecutive slots each)."""
+        per_set = max(1, self.k // per_launch)
+        st, slot = divmod(launch % (self.sets * per_set), per_set)
+        return self.xp[st] + slot * per_launch * self.xb, self.yp[st] + slot * per_launch * self.yb
+
+    def enqueue(self, first_step: int, n_steps: int, per_launch: int, n_streams: int = 1,
+                indices_at_step0: bool = True) -> int:
+        """Enqueues the batches [first_step, first_step + n_steps) of the run (step i = batch i mod nb of
+        epoch i div nb), per_launch of them per launch, alternating over n_streams caller streams;
+        the epoch's indices are generated when a step is the first batch of its epoch.  Returns the
+        number of snapshots built."""
+        handles = [self.stream.cuda_stream, self.side.cuda_stream][:n_streams]
+        snaps, i, launch, end = 0, first_step, 0, first_step + n_steps
+        while i < end:
+            e, b = divmod(i, self.nb)
+            if b == 0 and (indices_at_step0 or i != first_step):
+                self.gen_indices(self.w.epochs[0] + e)  # consecutive epochs
+            kk = min(per_launch, self.nb - b, end - i)
+            rc = self.build_raw(b, kk, *self.out_ptrs(launch, per_launch), handles[launch % n_streams])
+            if rc < 0:
+                raise RuntimeError(self.pgti.last_error())
+            snaps += rc
+            i += kk
+            launch += 1
+        return snaps
+
+    def steady_steps(self, n_steps: int, warmup: int, per_launch: int, n_streams: int = 1):
+        """Warm-up batches, then exactly n_steps further batches of the same run, timed on the host
+        clock between two device synchronisations."""
+        sync = self.torch.cuda.synchronize
+        self.enqueue(0, warmup, per_launch, n_streams)
+        sync()
+        t0 = time.perf_counter()
+        n = self.enqueue(warmup, n_steps, per_launch, n_streams, indices_at_step0=(warmup % self.nb == 0))
+        sync()
+        return n, time.perf_counter() - t0
+
+    def epochs(self, n_epochs: int, per_launch: int, n_streams: int = 1, with_indices: bool = True, reps: int = 3):
+        """n_epochs whole consecutive epochs; with_indices=False generates the first epoch's order
+        before the clock starts (later epochs of the pass generate theirs inside).  Median of reps."""
+        sync, times, snaps = self.torch.cuda.synchronize, [], 0
+        for _ in range(reps):
+            self.enqueue(0, min(self.nb, 2 * per_launch * n_streams), per_launch, n_streams)  # warm both streams
+            if not with_indices:
+                self.gen_indices(self.w.epochs[0])
+                self.ctx.get_indices()  # waits for the order
+            sync()
+            t0 = time.perf_counter()
+            snaps = self.enqueue(0, n_epochs * self.nb, per_launch, n_streams, indices_at_step0=with_indices)
+            sync()
+            times.append(time.perf_counter() - t0)
+        t = sorted(times)[len(times) // 2]
+        return {"value": snaps / t, "unit": "snapshots/s", "ms": t * 1e3, "epochs": n_epochs, "snapshots": snaps,
+                "gb_per_s": snaps * self.bps / t / 1e9, "pct_of_hbm_peak": snaps * self.bps / t / 1e9 / HBM_PEAK_GBS * 100,
+                "batches_per_launch": per_launch, "caller_streams": n_streams, "passes": reps}
+
+    def unique_bytes(self, per_launch: int) -> int:
+        """Bytes a launch of per_launch full batches must move when every distinct source row is
+        fetched once: the algorithmic bytes for the global shuffle (samples share no rows), one read of
+        B+P+Q-1 rows per batch plus all the writes for batches of consecutive starts."""
+        w = self.w
+        B = min(w.B, self.n_share)
+        if self.order == "shuffle":
+            return per_launch * B * self.bps
+        s_in = 4 if w.storage == "f32" else 2
+        return per_launch * ((B + w.P + w.Q - 1) * w.N * w.F * s_in + B * (w.P + w.Q) * w.N * w.F * self.out_elem)
+
+    def kernel_rate(self, per_launch: int, max_launches: int):
+        """Average duration of back-to-back launches of per_launch FULL batches, from HIP events on
+        the launch stream; only gather launches sit between the two events."""
+        torch = self.torch
+        self.gen_indices(self.w.epochs[0])
+        self.ctx.get_indices()  # waits for the sort
+        full_batches = max(1, self.nb - 1 if self.n_share % self.w.B else self.nb)
+        per_launch = min(per_launch, full_batches)
+        per_epoch = min(max(1, full_batches // per_launch), max_launches)
+        reps = max(1, min(64, max_launches // per_epoch))
+        ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        sh = self.stream.cuda_stream
+        for l in range(min(per_epoch, 16)):
+            self.build_raw(l * per_launch, per_launch, *self.out_ptrs(l, per_launch), sh)
+        torch.cuda.synchronize()
+        ev0.record(self.stream)
+        n = 0
+        for _ in range(reps):
+            for l in range(per_epoch):
+                self.build_raw(l * per_launch, per_launch, *self.out_ptrs(n, per_launch), sh)
+                n += 1
+        ev1.record(self.stream)
+        torch.cuda.synchronize()
+        avg_s = ev0.elapsed_time(ev1) * 1e-3 / n
+        alg = per_launch * min(self.w.B, self.n_share) * self.bps
+        moved = self.unique_bytes(per_launch)
+        # achieved = the bytes the launch has to move / its duration: the algorithmic bytes, except for
+        # batches of consecutive starts, where the row-centric kernel reads every shared row once
+        return {"kernel": self.kernel, "launches": n, "avg_launch_us": avg_s * 1e6, "batches_per_launch": per_launch,
+                "algorithmic_bytes_per_launch": alg, "unique_bytes_ideal_per_launch": moved,
+                "numerator": "algorithmic bytes" if moved == alg else "unique-bytes ideal (shared source rows read once)",
+                "achieved": moved / avg_s / 1e9, "frac": moved / avg_s / 1e9 / HBM_PEAK_GBS}
+
+    def index_generation_ms(self, n: int = 10) -> float:
+        self.torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for e in range(n):
+            self.gen_indices(100 + e)
+        self.ctx.get_indices()
+        return (time.perf_counter() - t0) / n * 1e3
+
+    def release(self):
+        self.xs = self.ys = None
+
+
+def other_workload(name: str, host_series, roofline_launches: int, side_stream):
+    """One timed pass of another benchmark configuration: its epochs back to back (index generation
+    included), the dominant kernel's rate, and pgti_build_batch one call per batch."""
+    import numpy as np
+    import torch
+    from paper_2507_11683_amd import pgti, workloads
+
+    w = workloads.WORKLOADS[name]
+    storage = pgti.PGTI_F32 if w.storage == "f32" else pgti.PGTI_BF16
+    series = host_series if host_series is not None else workloads.make_series(w)
+    with pgti.Context(0) as ctx:
+        ctx.load_series(series, w.P, w.Q, w.B, storage, None, None)  # channel-0 statistics on the device
+        mean, std = ctx.get_stats()
+        mean[1:], std[1:] = 0.0, 1.0
+        ctx.load_series(series, w.P, w.Q, w.B, storage, mean, std)
+        r = Runner(ctx, w, "shuffle", "f32", side_stream)
+        # small workloads: enough consecutive epochs that the pass lasts milliseconds, not microseconds
+        est = r.epochs(len(w.epochs), r.k, reps=1)
+        n_epochs = len(w.epochs) * max(1, min(200, int(10.0 / max(est["ms"], 1e-3))))
+        out = {"config": {"workload": w.name, "T": w.T, "N": w.N, "F": w.F, "P": w.P, "Q": w.Q, "B": w.B,
+                          "storage": w.storage, "world": w.world, "rank": w.rank, "seed": w.seed,
+                          "batches_per_epoch": r.nb, "snapshots_per_epoch": r.n_share,
+                          "algorithmic_bytes_per_snapshot": r.bps, "out_buffer_sets": r.sets},
+               "epochs_with_index_generation": r.epochs(n_epochs, r.k),
+               "roofline": r.kernel_rate(r.k, roofline_launches),
+               "one_batch_per_launch": {"one_stream": r.epochs(n_epochs, 1, 1),
+                                        "two_streams": r.epochs(n_epochs, 1, 2),
+                                        "roofline": r.kernel_rate(1, roofline_launches)},
+               "epoch_indices_ms": r.index_generation_ms()}
+        out["value"] = out["epochs_with_index_generation"]["value"]
+        out["unit"] = "snapshots/s"
+        r.release()
+    torch.cuda.synchronize()
+    return out
+
+
 def main():
     args = parse_args()
     if args.gpus != 1:
@@ -133,6 +345,7 @@ def main():
     w = workloads.WORKLOADS[args.workload]
     storage = pgti.PGTI_F32 if w.storage == "f32" else pgti.PGTI_BF16
     torch.cuda.set_device(0)
+    side_stream = torch.cuda.Stream()  # second caller stream of the two-stream legs, created before any context
 
     # ---- input: generated straight into pinned host memory, loaded once ----------------------
     t0 = time.perf_counter()
@@ -159,118 +372,52 @@ def main():
     ctx.load_series(host, w.P, w.Q, w.B, storage, mean, std)
     t_load2 = time.perf_counter() - t0
 
-    # ---- launch shape: k batches per launch (pgti_build_batches) -----------------------------------
-    order = {"shuffle": pgti.PGTI_ORDER_SHUFFLE, "sequential": pgti.PGTI_ORDER_SEQUENTIAL,
-             "batch_shuffle": pgti.PGTI_ORDER_BATCH_SHUFFLE}[args.order]
-
-    def gen_indices(epoch: int) -> int:
-        return ctx.epoch_indices_ex(order, seed=w.seed, epoch=epoch, rank=w.rank, world=w.world)
-
-    n_share = gen_indices(w.epochs[0])
-    nb = ctx.num_batches()
-    out_elem = 4 if args.out_dtype == "f32" else 2
-    out_torch = torch.float32 if args.out_dtype == "f32" else torch.bfloat16
-    bps = w.bytes_per_snapshot(out_elem)                  # algorithmic bytes per snapshot
-    batch_bytes = w.B * bps                               # algorithmic read + write of a full batch
-    out_bytes = w.B * (w.P + w.Q) * w.N * w.F * out_elem  # x + y of one batch
-    build_raw = ctx.build_batches_raw if args.out_dtype == "f32" else ctx.build_batches_bf16_raw
-    k = args.batches_per_launch or max(1, min(nb, -(-(512 << 20) // batch_bytes)))
-    if not args.batches_per_launch and args.order != "shuffle" and w.series_bytes_f32 > (256 << 20):
-        k = 1  # consecutive starts, write-bound row-centric kernel: measured fastest at one batch per launch
-    k = min(k, nb, 65535 // w.B)
-
-    # ---- output buffers: rotate enough sets that writes cannot sit in the 256 MB last-level cache --
-    sets = args.out_pairs or min(64, max(3, -(-(768 << 20) // (k * out_bytes))))
-    xs = [torch.empty((k, w.B, w.P, w.N, w.F), dtype=out_torch, device="cuda") for _ in range(sets)]
-    ys = [torch.empty((k, w.B, w.Q, w.N, w.F), dtype=out_torch, device="cuda") for _ in range(sets)]
-    xp, yp = [t.data_ptr() for t in xs], [t.data_ptr() for t in ys]
-    stream = torch.cuda.current_stream()
-    sh = stream.cuda_stream
+    r = Runner(ctx, w, args.order, args.out_dtype, side_stream, args.batches_per_launch, args.out_pairs)
+    k, nb = r.k, r.nb
     steps = args.steps or nb * len(w.epochs)
 
-    x_batch_bytes, y_batch_bytes = w.B * w.P * w.N * w.F * out_elem, w.B * w.Q * w.N * w.F * out_elem
-
-    def out_ptrs(launch: int, per_launch: int):
-        """Rotates launches over every slot of every set (per_launch consecutive slots each)."""
-        per_set = max(1, k // per_launch)
-        idx = launch % (sets * per_set)
-        st, slot = divmod(idx, per_set)
-        return xp[st] + slot * per_launch * x_batch_bytes, yp[st] + slot * per_launch * y_batch_bytes
-
-    def run(n_steps: int, per_launch: int) -> int:
-        """Enqueues n_steps batches (per_launch of them per launch), generating the indices at each
-        epoch boundary.  Returns the number of snapshots built."""
-        snaps, i, launch = 0, 0, 0
-        while i < n_steps:
-            e, b = divmod(i, nb)
-            if b == 0:
-                gen_indices(w.epochs[0] + e)  # consecutive epochs
-            kk = min(per_launch, nb - b, n_steps - i)
-            rc = build_raw(b, kk, *out_ptrs(launch, per_launch), sh)
-            if rc < 0:
-                raise RuntimeError(pgti.last_error())
-            snaps += rc
-            i += kk
-            launch += 1
-        return snaps
-
-    def timed(per_launch: int):
-        run(args.warmup, per_launch)
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        n = run(steps, per_launch)
-        torch.cuda.synchronize()
-        return n, time.perf_counter() - t0
-
-    def kernel_rate(per_launch: int):
-        """Average duration of back-to-back launches of per_launch FULL batches, from HIP events on
-        the launch stream; only gather launches sit between the two events."""
-        gen_indices(w.epochs[0])
-        ctx.get_indices()  # waits for the sort
-        full_batches = max(1, nb - 1 if n_share % w.B else nb)
-        per_launch = min(per_launch, full_batches)
-        per_epoch = max(1, full_batches // per_launch)
-        per_epoch = min(per_epoch, args.roofline_launches)
-        reps = max(1, min(64, args.roofline_launches // per_epoch))
-        ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        for l in range(min(per_epoch, 16)):
-            build_raw(l * per_launch, per_launch, *out_ptrs(l, per_launch), sh)
-        torch.cuda.synchronize()
-        ev0.record(stream)
-        n = 0
-        for _ in range(reps):
-            for l in range(per_epoch):
-                build_raw(l * per_launch, per_launch, *out_ptrs(n, per_launch), sh)
-                n += 1
-        ev1.record(stream)
-        torch.cuda.synchronize()
-        avg_s = ev0.elapsed_time(ev1) * 1e-3 / n
-        nbytes = per_launch * min(w.B, n_share) * bps
-        return {"launches": n, "avg_launch_us": avg_s * 1e6, "algorithmic_bytes_per_launch": nbytes,
-                "achieved": nbytes / avg_s / 1e9, "batches_per_launch": per_launch}
-
-    # ---- warm-up, timed region, kernel rate: k batches per launch, then one batch per launch -------
-    snaps, elapsed = timed(k)
+    # ---- the requested steps in the steady state of a run, k batches per launch ---------------------
+    snaps, elapsed = r.steady_steps(steps, args.warmup, k)
     repeat_values = []
     for _ in range(max(0, args.repeats)):
-        n_r, t_r = timed(k)
+        n_r, t_r = r.steady_steps(steps, args.warmup, k)
         repeat_values.append(n_r / t_r)
-    rate_k = kernel_rate(k)
-    snaps1, elapsed1 = timed(1) if k > 1 else (snaps, elapsed)
-    rate_1 = kernel_rate(1) if k > 1 else rate_k
+    rate_k = r.kernel_rate(k, args.roofline_launches)
+
+    # ---- whole epochs (the workload's own epoch list), with and without the index generation --------
+    n_ep = len(w.epochs)
+    full_epoch = {"with_index_generation": r.epochs(n_ep, k, with_indices=True),
+                  "without_index_generation": r.epochs(n_ep, k, with_indices=False)}
+
+    # ---- pgti_build_batch, one call per batch: one caller stream, two alternating caller streams ----
+    if k > 1:
+        snaps1, elapsed1 = r.steady_steps(steps, args.warmup, 1)
+        snaps2, elapsed2 = r.steady_steps(steps, args.warmup, 1, n_streams=2)
+        rate_1 = r.kernel_rate(1, args.roofline_launches)
+    else:
+        snaps1, elapsed1, rate_1 = snaps, elapsed, rate_k
+        snaps2, elapsed2 = r.steady_steps(steps, args.warmup, 1, n_streams=2)
+    one_batch = {
+        "value": snaps1 / elapsed1, "unit": "snapshots/s", "ms_per_step": elapsed1 / steps * 1e3,
+        "gb_per_s": snaps1 * r.bps / elapsed1 / 1e9,
+        "roofline": rate_1,
+        "full_epoch_one_stream": r.epochs(n_ep, 1, 1),
+        # independent batches alternated over two caller streams: the tail of one launch overlaps the
+        # ramp of the next (each stream is ordered behind the share by the library)
+        "two_streams": {"value": snaps2 / elapsed2, "unit": "snapshots/s", "ms_per_step": elapsed2 / steps * 1e3,
+                        "gb_per_s": snaps2 * r.bps / elapsed2 / 1e9},
+        "full_epoch_two_streams": r.epochs(n_ep, 1, 2),
+    }
 
     # ---- calibration copies for the counter runs (known size: reads and writes one x buffer) ----
     for _ in range(args.copy_calibration):
-        xs[1][0].copy_(xs[0][0])
+        r.xs[1][0].copy_(r.xs[0][0])
     torch.cuda.synchronize()
+    calib_bytes = r.xs[0][0].numel() * r.xs[0][0].element_size()
 
-    # ---- index generation alone ----------------------------------------------------------------
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for e in range(10):
-        gen_indices(100 + e)
-    ctx.get_indices()
-    t_idx = (time.perf_counter() - t0) / 10
+    t_idx = r.index_generation_ms()
+    traffic, traffic_source = traffic_from_profiles(w.name, args.order, args.out_dtype, rate_k["batches_per_launch"],
+                                                    rate_k["kernel"])
 
     result = {
         "metric": "snapshots/sec and achieved HBM GB/s (% of peak) for index-batched window build",
@@ -288,44 +435,52 @@ def main():
         "config": {"workload": w.name, "T": w.T, "N": w.N, "F": w.F, "P": w.P, "Q": w.Q, "B": w.B,
                    "storage": w.storage, "world": w.world, "rank": w.rank, "seed": w.seed,
                    "epochs": list(w.epochs), "batches_per_epoch": nb, "snapshots_timed": snaps,
-                   "batches_per_launch": k, "out_buffer_sets": sets, "order": args.order,
-                   "out_dtype": args.out_dtype, "algorithmic_bytes_per_snapshot": bps},
-        "gb_per_s": snaps * bps / elapsed / 1e9,
-        "pct_of_hbm_peak": snaps * bps / elapsed / 1e9 / HBM_PEAK_GBS * 100,
+                   "batches_per_launch": k, "out_buffer_sets": r.sets, "order": args.order,
+                   "out_dtype": args.out_dtype, "algorithmic_bytes_per_snapshot": r.bps,
+                   "timed_region": "steps are consecutive batches of a run in progress: the epoch's index list is "
+                                   "generated once per epoch, inside the timed steps only when they cross an epoch "
+                                   "boundary; full_epoch times a whole epoch with it"},
+        "gb_per_s": snaps * r.bps / elapsed / 1e9,
+        "pct_of_hbm_peak": snaps * r.bps / elapsed / 1e9 / HBM_PEAK_GBS * 100,
         "roofline": {
             "bound": "hbm", "achieved": rate_k["achieved"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
-            "frac": rate_k["achieved"] / HBM_PEAK_GBS, "traffic": traffic_from_profiles(w.name, k),
-            "kernel": "gather_quads_kernel", **{kk: v for kk, v in rate_k.items() if kk != "achieved"},
+            "frac": rate_k["frac"], "traffic": traffic, "traffic_source": traffic_source,
+            **{kk: v for kk, v in rate_k.items() if kk not in ("achieved", "frac")},
         },
-        # bytes a launch must move if every distinct source row is fetched once: equals the algorithmic
-        # bytes for the global shuffle (no shared rows), far fewer reads for consecutive starts
-        "unique_bytes_ideal_per_launch": (
-            rate_k["algorithmic_bytes_per_launch"] if args.order == "shuffle" else
-            (rate_k["batches_per_launch"] * w.B + w.P + w.Q - 1) * w.N * w.F * (4 if w.storage == "f32" else 2)
-            + rate_k["batches_per_launch"] * w.B * (w.P + w.Q) * w.N * w.F * out_elem),
-        "one_batch_per_launch": {
-            "value": snaps1 / elapsed1, "unit": "snapshots/s", "ms_per_step": elapsed1 / steps * 1e3,
-            "gb_per_s": snaps1 * bps / elapsed1 / 1e9,
-            "roofline": {"achieved": rate_1["achieved"], "frac": rate_1["achieved"] / HBM_PEAK_GBS,
-                         **{kk: v for kk, v in rate_1.items() if kk != "achieved"}},
-        },
+        "full_epoch": full_epoch,
+        "one_batch_per_launch": one_batch,
         # the same K steps timed again (each pass with its own warm-up and synchronisation): run-to-run spread
         "repeats": {"count": len(repeat_values), "unit": "snapshots/s",
                     "median": float(sorted(repeat_values)[len(repeat_values) // 2]) if repeat_values else None,
                     "min": min(repeat_values) if repeat_values else None,
                     "max": max(repeat_values) if repeat_values else None},
-        "epoch_indices_ms": t_idx * 1e3,
-        "copy_calibration": {"count": args.copy_calibration, "bytes_read": xs[0][0].numel() * xs[0][0].element_size(),
-                             "bytes_written": xs[0][0].numel() * xs[0][0].element_size()},
+        "epoch_indices_ms": t_idx,
+        "copy_calibration": {"count": args.copy_calibration, "bytes_read": calib_bytes, "bytes_written": calib_bytes},
         "setup": {"generate_s": t_gen, "load_with_device_stats_s": t_load, "load_s": t_load2,
                   "load_with_alg1_train_stats_s": t_load_alg1,
                   "alg1_train_mean_std": [float(alg1_mean[0]), float(alg1_std[0])],
                   "series_bytes": w.series_bytes_f32, "load_gb_per_s": w.series_bytes_f32 / t_load2 / 1e9},
     }
+    r.release()
     ctx.destroy()
-    del xs, ys
+    torch.cuda.synchronize()
+
+    # ---- the other benchmark configurations, one timed pass each --------------------------------------
+    if not args.no_other_workloads:
+        others = {}
+        for name in workloads.WORKLOADS:
+            if name == w.name:
+                continue
+            ow = workloads.WORKLOADS[name]
+            same_series = (ow.T, ow.N, ow.F, ow.data_seed, ow.gen_flags) == (w.T, w.N, w.F, w.data_seed, w.gen_flags)
+            t0 = time.perf_counter()
+            others[name] = other_workload(name, host if same_series else None, min(args.roofline_launches, 2048),
+                                          side_stream)
+            others[name]["wall_s"] = time.perf_counter() - t0
+        result["other_workloads"] = others
+
     if not args.no_cpu_baseline:
-        result["cpu_baseline"] = cpu_baseline(w, series, mean, std, args.cpu_batches, order)
+        result["cpu_baseline"] = cpu_baseline(w, series, mean, std, args.cpu_batches, r.order_code)
     print(json.dumps(result))
 
 

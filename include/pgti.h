@@ -68,8 +68,12 @@ void pgti_destroy(pgti_ctx* c);
  * (Algorithm 1 standardises with (v - mu) / sigma).  If BOTH are NULL the library computes, on
  * the device, the mean and the population standard deviation of every feature over all T*N
  * values of the fp32 input.  Exactly one of them NULL is PGTI_ERR_ARG.
- * Replaces any series loaded before (after waiting for batch builds still in flight on it);
- * invalidates epoch indices.  Synchronous: on return the host buffers are no longer referenced.
+ * Replaces any series loaded before (after waiting for batch builds still in flight on it) and
+ * invalidates its epoch indices -- but only when the load succeeds: the new store is built beside
+ * the old one and swapped in at the end, so on ANY error the context keeps its previous series,
+ * statistics and share and stays usable.  During the call both series occupy device memory; to
+ * replace a series whose successor does not fit beside it, destroy the context and create a new one.
+ * Synchronous: on return the host buffers are no longer referenced.
  * Errors: ARG, RANGE (T < P + Q, or n >= 2^31), STATS, OOM, HIP.
  */
 int pgti_load_series(pgti_ctx* c, const float* host_series, int64_t T, int32_t N, int32_t F,
@@ -77,7 +81,11 @@ int pgti_load_series(pgti_ctx* c, const float* host_series, int64_t T, int32_t N
                      const float* std);
 
 /* Same as pgti_load_series but the fp32 source already lives in DEVICE memory (for a caller
- * that produced or staged the series on the GPU).  The source is not modified or retained. */
+ * that produced or staged the series on the GPU).  The source is not modified or retained.
+ * Ordering: the library reads the source on a stream of its own, so before the first read it waits
+ * (hipDeviceSynchronize) for all work enqueued on the device so far, whatever stream produced the
+ * series; work that writes the source must have been enqueued before this call.  The same holds
+ * for pgti_load_series_ex with source_on_device != 0. */
 int pgti_load_series_device(pgti_ctx* c, const float* device_series, int64_t T, int32_t N,
                             int32_t F, int32_t P, int32_t Q, int32_t B, pgti_dtype storage,
                             const float* mean, const float* std);
@@ -241,6 +249,15 @@ int64_t pgti_num_batches(pgti_ctx* c);
  * is kernel launches only and may be recorded into a HIP graph by stream capture.  Such a graph
  * stays valid for later epochs of the same share length (its arguments do not change); replay it
  * behind one ordinary build on the same stream, which supplies the wait.
+ * Streams: the context tracks up to 8 distinct streams between two index generations without
+ * blocking; a build on a ninth distinct stream first waits ON THE HOST (hipStreamSynchronize) for
+ * the oldest tracked stream and takes its slot.
+ * Throughput: consecutive launches on ONE stream are dependent, and on MI355X the drain of one
+ * launch plus the ramp of the next costs about 2.4 us per launch (a 23 us Statewide batch: 73 % of
+ * the HBM peak).  Batches are independent, so a caller that wants one call per batch should
+ * alternate its calls over TWO streams (batch b on stream b mod 2; 79 % measured), provided the two
+ * streams sit on different hardware queues (HIP deals streams onto a few queues in creation
+ * order); or build several batches per launch with pgti_build_batches.
  * Returns the number of valid samples B' in 1..B.  A short last batch is not padded: rows
  * j >= B' of the outputs are left untouched.
  * Errors: STATE, RANGE (batch_no outside [0, num_batches)), ARG (null or misaligned), HIP.

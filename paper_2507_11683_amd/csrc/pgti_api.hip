@@ -55,6 +55,45 @@ void free_series(pgti_ctx* c) {
     c->series_bytes = 0;
 }
 
+// Moves the resident store (device buffers, geometry, statistics) of `from` into `to`, whose own
+// store must have been freed; `from` is left empty.
+void adopt_store(pgti_ctx* to, pgti_ctx* from) {
+    auto take = [](auto*& dst, auto*& src) {
+        dst = src;
+        src = nullptr;
+    };
+    take(to->d_series, from->d_series);
+    take(to->d_stats, from->d_stats);
+    for (int k = 0; k < 2; ++k) {
+        take(to->d_keys[k], from->d_keys[k]);
+        take(to->d_vals[k], from->d_vals[k]);
+        take(to->d_hist[k], from->d_hist[k]);
+    }
+    take(to->d_tot, from->d_tot);
+    take(to->d_bucket, from->d_bucket);
+    take(to->d_share, from->d_share);
+    take(to->d_share_next, from->d_share_next);
+    to->series_bytes = from->series_bytes;
+    to->sort_blocks = from->sort_blocks;
+    to->mean = from->mean;
+    to->stdev = from->stdev;
+    to->recip = from->recip;
+    to->fast_divide = from->fast_divide;
+    to->T = from->T;
+    to->N = from->N;
+    to->F = from->F;
+    to->P = from->P;
+    to->Q = from->Q;
+    to->B = from->B;
+    to->R = from->R;
+    to->storage = from->storage;
+    to->n_windows = from->n_windows;
+    to->path = from->path;
+    to->loaded = from->loaded;
+    to->have_share = false;
+    from->loaded = false;
+}
+
 // Temporary device / pinned buffers of one load, released on every exit path.
 struct LoadScratch {
     void* pinned[2] = {nullptr, nullptr};
@@ -156,10 +195,20 @@ int load_impl(pgti_ctx* c, const float* src, const pgti_load_spec* spec) {
     if (guard.status != hipSuccess) return fail_hip(guard.status, "hipSetDevice");
     hipStream_t ws = c->work_stream;
     PGTI_HIP_TRY(hipStreamSynchronize(ws));
-    // Batch builds enqueued through this context may still read the series that is about to go.
-    for (int k = 0; k < c->n_tracked; ++k) PGTI_HIP_TRY(hipStreamSynchronize(c->tracked[k].stream));
-    free_series(c);
-    c->n_tracked = 0;
+    // A source that lives on the device may still be being written by work the caller enqueued on
+    // any of its streams: wait for all of it before the first read (the load is synchronous anyway).
+    if (src_on_device) PGTI_HIP_TRY(hipDeviceSynchronize());
+
+    // The new store is built beside the old one and replaces it only when everything has succeeded:
+    // a failed load leaves the context exactly as it was.  `fresh` is released on every early return.
+    pgti_ctx fresh_store;
+    pgti_ctx* nx = &fresh_store;
+    struct Release {
+        pgti_ctx* store;
+        ~Release() {
+            if (store) free_series(store);
+        }
+    } release{nx};
 
     const int64_t R = static_cast<int64_t>(N) * F, R_in = static_cast<int64_t>(N) * F_in;
     const size_t elems = static_cast<size_t>(T) * R;
@@ -169,32 +218,32 @@ int load_impl(pgti_ctx* c, const float* src, const pgti_load_spec* spec) {
         hipError_t e = hipMalloc(reinterpret_cast<void**>(p), bytes < 256 ? 256 : bytes);
         if (e == hipErrorOutOfMemory) {
             (void)hipGetLastError();
-            free_series(c);
+            free_series(nx);
             return fail(PGTI_ERR_OOM, "device allocation of %zu bytes failed", bytes);
         }
         if (e != hipSuccess) {
-            free_series(c);
+            free_series(nx);
             return fail_hip(e, "hipMalloc");
         }
         return PGTI_OK;
     };
 
     const uint32_t nblk = static_cast<uint32_t>((n + kSortTile - 1) / kSortTile);
-    if (int rc = alloc(&c->d_series, elems * store_bytes)) return rc;
-    if (int rc = alloc(&c->d_stats, sizeof(float) * 3 * F)) return rc;
-    if (int rc = alloc(&c->d_keys[0], sizeof(uint64_t) * n)) return rc;
-    if (int rc = alloc(&c->d_keys[1], sizeof(uint64_t) * n)) return rc;
-    if (int rc = alloc(&c->d_vals[0], sizeof(int32_t) * n)) return rc;
-    if (int rc = alloc(&c->d_vals[1], sizeof(int32_t) * n)) return rc;
-    if (int rc = alloc(&c->d_hist[0], sizeof(uint32_t) * 256 * nblk)) return rc;
-    if (int rc = alloc(&c->d_hist[1], sizeof(uint32_t) * 256 * nblk)) return rc;
-    if (int rc = alloc(&c->d_tot, sizeof(uint32_t) * 256)) return rc;
-    if (int rc = alloc(&c->d_bucket, sizeof(uint32_t) * kSortBucketWords)) return rc;
-    PGTI_HIP_TRY(hipMemsetAsync(c->d_bucket, 0, sizeof(uint32_t) * kSortBucketWords, ws));
-    if (int rc = alloc(&c->d_share, sizeof(int32_t) * n)) return rc;
-    if (int rc = alloc(&c->d_share_next, sizeof(int32_t) * n)) return rc;
-    c->series_bytes = elems * store_bytes;
-    c->sort_blocks = nblk;
+    if (int rc = alloc(&nx->d_series, elems * store_bytes)) return rc;
+    if (int rc = alloc(&nx->d_stats, sizeof(float) * 3 * F)) return rc;
+    if (int rc = alloc(&nx->d_keys[0], sizeof(uint64_t) * n)) return rc;
+    if (int rc = alloc(&nx->d_keys[1], sizeof(uint64_t) * n)) return rc;
+    if (int rc = alloc(&nx->d_vals[0], sizeof(int32_t) * n)) return rc;
+    if (int rc = alloc(&nx->d_vals[1], sizeof(int32_t) * n)) return rc;
+    if (int rc = alloc(&nx->d_hist[0], sizeof(uint32_t) * 256 * nblk)) return rc;
+    if (int rc = alloc(&nx->d_hist[1], sizeof(uint32_t) * 256 * nblk)) return rc;
+    if (int rc = alloc(&nx->d_tot, sizeof(uint32_t) * 256)) return rc;
+    if (int rc = alloc(&nx->d_bucket, sizeof(uint32_t) * kSortBucketWords)) return rc;
+    PGTI_HIP_TRY(hipMemsetAsync(nx->d_bucket, 0, sizeof(uint32_t) * kSortBucketWords, ws));
+    if (int rc = alloc(&nx->d_share, sizeof(int32_t) * n)) return rc;
+    if (int rc = alloc(&nx->d_share_next, sizeof(int32_t) * n)) return rc;
+    nx->series_bytes = elems * store_bytes;
+    nx->sort_blocks = nblk;
 
     // Rows per chunk: about 64 MiB of fp32, a multiple of 4 rows so that every chunk starts on a
     // 16-byte boundary whatever R is.
@@ -214,7 +263,7 @@ int load_impl(pgti_ctx* c, const float* src, const pgti_load_spec* spec) {
             hipError_t e = hipHostMalloc(&tmp.pinned[k], chunk_bytes_in, hipHostMallocDefault);
             if (e != hipSuccess) {
                 (void)hipGetLastError();
-                free_series(c);
+                free_series(nx);
                 return fail(PGTI_ERR_OOM, "pinned staging allocation of %zu bytes failed", chunk_bytes_in);
             }
         }
@@ -239,7 +288,7 @@ int load_impl(pgti_ctx* c, const float* src, const pgti_load_spec* spec) {
             const int64_t rows = (T - row0 < chunk_rows) ? (T - row0) : chunk_rows;
             const size_t off = static_cast<size_t>(row0) * R, off_in = static_cast<size_t>(row0) * R_in;
             const size_t cnt = static_cast<size_t>(rows) * R, cnt_in = static_cast<size_t>(rows) * R_in;
-            float* resident32 = static_cast<float*>(c->d_series) + off;  // meaningful for fp32 storage
+            float* resident32 = static_cast<float*>(nx->d_series) + off;  // meaningful for fp32 storage
 
             // the source chunk on the device, when this sweep needs it
             const float* src_chunk = nullptr;
@@ -274,7 +323,7 @@ int load_impl(pgti_ctx* c, const float* src, const pgti_load_spec* spec) {
                     PGTI_HIP_TRY(launch_row_sums(src_chunk, rows, N, F, F_in, period, row0,
                                                  sweep == 1 ? tmp.stat64 : nullptr, tmp.row_acc, ws));
                 if (last_sweep) {
-                    uint16_t* resident16 = static_cast<uint16_t*>(c->d_series) + off;
+                    uint16_t* resident16 = static_cast<uint16_t*>(nx->d_series) + off;
                     if (synth)
                         PGTI_HIP_TRY(launch_assemble_rows(src_chunk, rows, N, F_in, F, row0, period, resident16, true, ws));
                     else
@@ -286,7 +335,7 @@ int load_impl(pgti_ctx* c, const float* src, const pgti_load_spec* spec) {
         }
         if (need_stats) {
             // mean after sweep 0 (kept in fp64 on the device for sweep 1), std after sweep 1
-            float* out32 = c->d_stats + (sweep == 0 ? 0 : F);
+            float* out32 = nx->d_stats + (sweep == 0 ? 0 : F);
             if (spec->stats_rule == PGTI_STATS_ALG1_TRAIN)
                 PGTI_HIP_TRY(launch_reduce_rows_alg1(tmp.row_acc, F, n_train, P,
                                                      static_cast<double>(n_train) * P * static_cast<double>(R),
@@ -297,49 +346,57 @@ int load_impl(pgti_ctx* c, const float* src, const pgti_load_spec* spec) {
         PGTI_HIP_TRY(hipStreamSynchronize(ws));
     }
 
-    c->mean.assign(F, 0.0f);
-    c->stdev.assign(F, 1.0f);
+    nx->mean.assign(F, 0.0f);
+    nx->stdev.assign(F, 1.0f);
     if (need_stats) {
-        PGTI_HIP_TRY(hipMemcpy(c->mean.data(), c->d_stats, sizeof(float) * F, hipMemcpyDeviceToHost));
-        PGTI_HIP_TRY(hipMemcpy(c->stdev.data(), c->d_stats + F, sizeof(float) * F, hipMemcpyDeviceToHost));
-        if (int rc = check_stats(c->mean.data(), c->stdev.data(), F)) {
-            free_series(c);
+        PGTI_HIP_TRY(hipMemcpy(nx->mean.data(), nx->d_stats, sizeof(float) * F, hipMemcpyDeviceToHost));
+        PGTI_HIP_TRY(hipMemcpy(nx->stdev.data(), nx->d_stats + F, sizeof(float) * F, hipMemcpyDeviceToHost));
+        if (int rc = check_stats(nx->mean.data(), nx->stdev.data(), F)) {
+            free_series(nx);
             return rc;
         }
     } else {
-        memcpy(c->mean.data(), mean, sizeof(float) * F);
-        memcpy(c->stdev.data(), stdev, sizeof(float) * F);
-        PGTI_HIP_TRY(hipMemcpy(c->d_stats, c->mean.data(), sizeof(float) * F, hipMemcpyHostToDevice));
-        PGTI_HIP_TRY(hipMemcpy(c->d_stats + F, c->stdev.data(), sizeof(float) * F, hipMemcpyHostToDevice));
+        memcpy(nx->mean.data(), mean, sizeof(float) * F);
+        memcpy(nx->stdev.data(), stdev, sizeof(float) * F);
+        PGTI_HIP_TRY(hipMemcpy(nx->d_stats, nx->mean.data(), sizeof(float) * F, hipMemcpyHostToDevice));
+        PGTI_HIP_TRY(hipMemcpy(nx->d_stats + F, nx->stdev.data(), sizeof(float) * F, hipMemcpyHostToDevice));
     }
 
     // Reciprocals for the gather's fast division: 1/sigma in fp64 rounded once to fp32 is the
     // correctly rounded fp32 reciprocal (53 >= 2*24 + 2 bits).  The fast path needs every sigma's
     // biased exponent in [95, 159]; otherwise the kernels divide the ordinary way.
-    c->recip.assign(F, 1.0f);
-    c->fast_divide = true;
+    nx->recip.assign(F, 1.0f);
+    nx->fast_divide = true;
     for (int32_t f = 0; f < F; ++f) {
         uint32_t bits;
-        memcpy(&bits, &c->stdev[f], 4);
+        memcpy(&bits, &nx->stdev[f], 4);
         const uint32_t expo = (bits >> 23) & 0xFFu;
-        if (expo < 95u || expo > 159u) c->fast_divide = false;
-        c->recip[f] = static_cast<float>(1.0 / static_cast<double>(c->stdev[f]));
+        if (expo < 95u || expo > 159u) nx->fast_divide = false;
+        nx->recip[f] = static_cast<float>(1.0 / static_cast<double>(nx->stdev[f]));
     }
-    PGTI_HIP_TRY(hipMemcpy(c->d_stats + 2 * F, c->recip.data(), sizeof(float) * F, hipMemcpyHostToDevice));
+    PGTI_HIP_TRY(hipMemcpy(nx->d_stats + 2 * F, nx->recip.data(), sizeof(float) * F, hipMemcpyHostToDevice));
 
-    c->T = T;
-    c->N = N;
-    c->F = F;
-    c->P = P;
-    c->Q = Q;
-    c->B = B;
-    c->R = R;
-    c->storage = storage;
-    c->n_windows = n;
+    nx->T = T;
+    nx->N = N;
+    nx->F = F;
+    nx->P = P;
+    nx->Q = Q;
+    nx->B = B;
+    nx->R = R;
+    nx->storage = storage;
+    nx->n_windows = n;
     const bool quad_ok = ((static_cast<int64_t>(P) * R) % 4 == 0) && ((static_cast<int64_t>(Q) * R) % 4 == 0);
-    c->path = quad_ok ? GatherPath::kQuads : GatherPath::kScalar;
-    c->loaded = true;
-    c->have_share = false;
+    nx->path = quad_ok ? GatherPath::kQuads : GatherPath::kScalar;
+    nx->loaded = true;
+    nx->have_share = false;
+
+    // Success: batch builds enqueued through this context may still read the old series; wait for
+    // them, free it, and adopt the new store.
+    for (int k = 0; k < c->n_tracked; ++k) PGTI_HIP_TRY(hipStreamSynchronize(c->tracked[k].stream));
+    c->n_tracked = 0;
+    free_series(c);
+    adopt_store(c, nx);
+    release.store = nullptr;
     return PGTI_OK;
 }
 

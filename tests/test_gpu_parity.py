@@ -596,6 +596,66 @@ def test_next_sort_overlaps_running_builds():
                 assert _bits_equal(gx[first:first + len(st)], wx) and _bits_equal(gy[first:first + len(st)], wy), (e, first)
 
 
+def test_one_batch_per_call_on_two_alternating_streams_statewide(statewide_series):
+    # The launch pattern the benchmark reports under one_batch_per_launch.two_streams, at full size:
+    # pgti_build_batch once per batch, consecutive batches alternating over two caller streams (so the
+    # tail of one launch overlaps the start of the next), each batch into its own buffers, no host
+    # synchronisation until the end; then a second epoch through the same streams.
+    w = workloads.WORKLOADS["statewide"]
+    mean, std = _sampled_stats(statewide_series)
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    with pgti.Context(0) as ctx:
+        ctx.load_series(statewide_series, w.P, w.Q, w.B, pgti.PGTI_F32, mean, std)
+        for epoch in (0, 1):
+            ctx.epoch_indices(w.seed, epoch)
+            nb = ctx.num_batches()
+            picks = [0, 1, 2, 3, nb // 2, nb // 2 + 1, nb - 3, nb - 2, nb - 1]
+            outs = [_alloc_out(w.B, w.P, w.Q, w.N, w.F, fill=12345.0) for _ in picks]
+            for i, b in enumerate(picks):
+                print("two streams: epoch", epoch, "batch", b, flush=True)
+                ctx.build_batch(b, outs[i][0], outs[i][1], stream=streams[i % 2])
+            torch.cuda.synchronize()
+            share = oracle.epoch_indices(w.seed, epoch, 0, 1, w.n_windows)
+            for (x, y), b in zip(outs, picks):
+                st = share[b * w.B:(b + 1) * w.B]
+                wx, wy = oracle.build_batch(statewide_series, oracle.F32, w.P, w.Q, mean, std, st)
+                gx, gy = x.cpu().numpy(), y.cpu().numpy()
+                assert _bits_equal(gx[:len(st)], wx) and _bits_equal(gy[:len(st)], wy), (epoch, b)
+                assert np.all(gx[len(st):] == 12345.0) and np.all(gy[len(st):] == 12345.0)
+            del outs
+
+
+def test_whole_epochs_on_two_alternating_streams_without_host_sync():
+    # Medium: three whole epochs, one pgti_build_batch per batch alternating over two streams, the
+    # next epoch's indices requested while builds are in flight on both; every batch of every epoch
+    # lands in its own slot and must be that epoch's batch.
+    w = workloads.WORKLOADS["medium"]
+    series = workloads.make_series(w)
+    mean, std = oracle.series_stats(series)
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    epochs = range(3)
+    with pgti.Context(0) as ctx:
+        ctx.load_series(series, w.P, w.Q, w.B, pgti.PGTI_F32, mean, std)
+        ctx.epoch_indices(33, 0)
+        nb = ctx.num_batches()
+        xs = [torch.zeros((nb, w.B, w.P, w.N, w.F), device="cuda") for _ in epochs]
+        ys = [torch.zeros((nb, w.B, w.Q, w.N, w.F), device="cuda") for _ in epochs]
+        torch.cuda.synchronize()
+        for e in epochs:
+            ctx.epoch_indices(33, e)
+            for b in range(nb):
+                ctx.build_batch(b, xs[e][b], ys[e][b], stream=streams[b % 2])
+        torch.cuda.synchronize()
+        for e in epochs:
+            share = oracle.epoch_indices(33, e, 0, 1, w.n_windows)
+            gx = xs[e].cpu().numpy().reshape(nb * w.B, w.P, w.N, w.F)
+            gy = ys[e].cpu().numpy().reshape(nb * w.B, w.Q, w.N, w.F)
+            for first in range(0, w.n_windows, 4096):
+                st = share[first:first + 4096]
+                wx, wy = oracle.build_batch(series, oracle.F32, w.P, w.Q, mean, std, st)
+                assert _bits_equal(gx[first:first + len(st)], wx) and _bits_equal(gy[first:first + len(st)], wy), (e, first)
+
+
 def test_more_streams_than_tracked_slots():
     # the context tracks 8 streams between two index generations; builds on 11 streams still order
     # correctly against the next sort and give the right batches
@@ -999,6 +1059,59 @@ def test_device_resident_source():
         ctx.load_series(pinned, w.P, w.Q, w.B, pgti.PGTI_F32, mean, std)
         ctx.epoch_indices(0, 0)
         _check_batches(ctx, series, pgti.PGTI_F32, w.P, w.Q, w.B, mean, std, ctx.get_indices(), [3])
+
+
+def test_device_source_still_being_written_on_a_side_stream():
+    # The series is produced on the device by asynchronous work on a side stream that is still in
+    # flight when the load is called (about 20 ms of copies are queued in front of the write of
+    # the source).  The load orders itself behind everything enqueued before it.
+    w = workloads.WORKLOADS["tiny"]
+    series = workloads.make_series(w)
+    mean, std = oracle.series_stats(series)
+    side = torch.cuda.Stream()
+    staged = torch.from_numpy(series).cuda()
+    dev = torch.zeros_like(staged)
+    ballast = torch.empty(1 << 29, dtype=torch.float32, device="cuda")  # 2 GiB
+    sink = torch.empty_like(ballast)
+    torch.cuda.synchronize()
+    for storage in (pgti.PGTI_F32, pgti.PGTI_BF16):
+        dev.zero_()
+        torch.cuda.synchronize()
+        with torch.cuda.stream(side):
+            for _ in range(16):
+                sink.copy_(ballast, non_blocking=True)
+            dev.copy_(staged, non_blocking=True)
+        with pgti.Context(0) as ctx:
+            ctx.load_series(dev, w.P, w.Q, w.B, storage, mean, std)  # no host synchronisation before it
+            ctx.epoch_indices(0, 0)
+            share = ctx.get_indices()
+            _check_batches(ctx, _oracle_series(series, storage), storage, w.P, w.Q, w.B, mean, std, share, [0, 17, 30])
+
+
+def test_failed_load_keeps_the_previous_series():
+    # a load that fails (statistics, range, arguments) leaves the loaded series, its statistics and
+    # its share in place: batches of the old share still build and match the oracle
+    w = workloads.WORKLOADS["tiny"]
+    series = workloads.make_series(w)
+    mean, std = oracle.series_stats(series)
+    constant = np.zeros((64, 4, 2), np.float32)
+    with pgti.Context(0) as ctx:
+        ctx.load_series(series, w.P, w.Q, w.B, pgti.PGTI_F32, mean, std)
+        ctx.epoch_indices(3, 1)
+        share = ctx.get_indices()
+        for bad in (lambda: ctx.load_series(constant, 12, 12, 4, pgti.PGTI_F32, None, None),       # sigma == 0
+                    lambda: ctx.load_series(constant, 40, 40, 4, pgti.PGTI_F32, [0, 0], [1, 1]),   # T < P + Q
+                    lambda: ctx.load_series(constant, 12, 12, 4, pgti.PGTI_BF16, [0, 0], [1, 0]),  # given sigma 0
+                    lambda: ctx.load_series_ex(constant, 12, 12, 4, stats_rule=pgti.PGTI_STATS_ALG1_TRAIN)):
+            with pytest.raises(pgti.PgtiError):
+                bad()
+            m, s_ = ctx.get_stats()
+            assert np.array_equal(m, mean) and np.array_equal(s_, std)
+            assert np.array_equal(ctx.get_indices(), share)
+            _check_batches(ctx, series, pgti.PGTI_F32, w.P, w.Q, w.B, mean, std, share, [0, 30])
+        # and a successful load afterwards replaces it
+        ctx.load_series(constant, 12, 12, 4, pgti.PGTI_F32, [0, 0], [1, 1])
+        assert ctx.epoch_indices(0, 0) == 64 - 24 + 1
 
 
 # ----------------------------------------------------------------------------------------------
