@@ -245,11 +245,12 @@ int load_impl(pgti_ctx* c, const float* src, const pgti_load_spec* spec) {
     nx->series_bytes = elems * store_bytes;
     nx->sort_blocks = nblk;
 
-    // Rows per chunk: about 64 MiB of fp32, a multiple of 4 rows so that every chunk starts on a
-    // 16-byte boundary whatever R is.
+    // A device source is taken in one piece.  A host source moves in chunks of about 64 MiB of fp32,
+    // a multiple of 4 rows so that every chunk starts on a 16-byte boundary whatever R is.
     int64_t chunk_rows = (64ll << 20) / (R * 4);
     chunk_rows = (chunk_rows / 4) * 4;
     if (chunk_rows < 4) chunk_rows = 4;
+    if (src_on_device) chunk_rows = T;
     const size_t chunk_bytes_in = static_cast<size_t>(chunk_rows) * R_in * 4;
 
     LoadScratch tmp;
@@ -278,21 +279,29 @@ int load_impl(pgti_ctx* c, const float* src, const pgti_load_spec* spec) {
     // Sweep 0 moves the data (and sums values if statistics are wanted); sweep 1, only with
     // statistics, sums squared deviations from the mean.  Statistics always see fp32 values: with
     // fp32 storage the finished resident rows, with bf16 storage the source chunk (the time-of-day
-    // channel synthesised on the fly); the bf16 rounding happens in the last sweep.
+    // channel synthesised on the fly); the bf16 rounding happens in the last sweep.  Every chunk is
+    // ONE kernel: it writes the resident rows and takes the row sums from the same registers.
     const int sweeps = need_stats ? 2 : 1;
+    double* const row_acc = need_stats ? tmp.row_acc : nullptr;
     for (int sweep = 0; sweep < sweeps; ++sweep) {
         const bool last_sweep = (sweep == sweeps - 1);
-        int slot = 0;
-        bool slot_busy[2] = {false, false};
-        for (int64_t row0 = 0; row0 < T; row0 += chunk_rows, slot ^= 1) {
-            const int64_t rows = (T - row0 < chunk_rows) ? (T - row0) : chunk_rows;
-            const size_t off = static_cast<size_t>(row0) * R, off_in = static_cast<size_t>(row0) * R_in;
-            const size_t cnt = static_cast<size_t>(rows) * R, cnt_in = static_cast<size_t>(rows) * R_in;
-            float* resident32 = static_cast<float*>(nx->d_series) + off;  // meaningful for fp32 storage
+        const double* const mean64 = (need_stats && sweep == 1) ? tmp.stat64 : nullptr;
+        if (storage == PGTI_F32 && sweep == 1) {
+            // the whole resident series in one launch
+            PGTI_HIP_TRY(launch_ingest_rows(static_cast<const float*>(nx->d_series), T, N, F, F, 0, 0, nullptr, false,
+                                            mean64, row_acc, ws));
+        } else {
+            int slot = 0;
+            bool slot_busy[2] = {false, false};
+            for (int64_t row0 = 0; row0 < T; row0 += chunk_rows, slot ^= 1) {
+                const int64_t rows = (T - row0 < chunk_rows) ? (T - row0) : chunk_rows;
+                const size_t off = static_cast<size_t>(row0) * R, off_in = static_cast<size_t>(row0) * R_in;
+                const size_t cnt_in = static_cast<size_t>(rows) * R_in;
+                float* resident32 = static_cast<float*>(nx->d_series) + off;        // fp32 storage
+                uint16_t* resident16 = static_cast<uint16_t*>(nx->d_series) + off;  // bf16 storage
 
-            // the source chunk on the device, when this sweep needs it
-            const float* src_chunk = nullptr;
-            if (sweep == 0 || storage == PGTI_BF16) {
+                // the source chunk on the device
+                const float* src_chunk = nullptr;
                 if (src_on_device) {
                     src_chunk = src + off_in;
                 } else {
@@ -306,32 +315,18 @@ int load_impl(pgti_ctx* c, const float* src, const pgti_load_spec* spec) {
                     PGTI_HIP_TRY(hipMemcpyAsync(dst, from, cnt_in * 4, hipMemcpyHostToDevice, ws));
                     src_chunk = dst;
                 }
-            }
 
-            if (storage == PGTI_F32) {
-                if (sweep == 0) {
-                    if (synth)
-                        PGTI_HIP_TRY(launch_assemble_rows(src_chunk, rows, N, F_in, F, row0, period, resident32, false, ws));
-                    else if (src_on_device)
-                        PGTI_HIP_TRY(hipMemcpyAsync(resident32, src_chunk, cnt * 4, hipMemcpyDeviceToDevice, ws));
+                void* out = nullptr;
+                if (storage == PGTI_F32) {
+                    if (src_chunk != resident32) out = resident32;  // else the copy has put the rows in place
+                } else if (last_sweep) {
+                    out = resident16;
                 }
-                if (need_stats)
-                    PGTI_HIP_TRY(launch_row_sums(resident32, rows, N, F, F, 0, row0, sweep == 1 ? tmp.stat64 : nullptr,
-                                                 tmp.row_acc, ws));
-            } else {
-                if (need_stats)
-                    PGTI_HIP_TRY(launch_row_sums(src_chunk, rows, N, F, F_in, period, row0,
-                                                 sweep == 1 ? tmp.stat64 : nullptr, tmp.row_acc, ws));
-                if (last_sweep) {
-                    uint16_t* resident16 = static_cast<uint16_t*>(nx->d_series) + off;
-                    if (synth)
-                        PGTI_HIP_TRY(launch_assemble_rows(src_chunk, rows, N, F_in, F, row0, period, resident16, true, ws));
-                    else
-                        PGTI_HIP_TRY(launch_store_bf16(src_chunk, resident16, cnt, ws));
-                }
+                PGTI_HIP_TRY(launch_ingest_rows(src_chunk, rows, N, F, F_in, period, row0, out, storage == PGTI_BF16,
+                                                mean64, row_acc, ws));
+                PGTI_HIP_TRY(hipEventRecord(tmp.done[slot], ws));
+                slot_busy[slot] = true;
             }
-            PGTI_HIP_TRY(hipEventRecord(tmp.done[slot], ws));
-            slot_busy[slot] = true;
         }
         if (need_stats) {
             // mean after sweep 0 (kept in fp64 on the device for sweep 1), std after sweep 1

@@ -84,24 +84,22 @@ void clear_error();
     } while (0)
 
 // ---- series_store.hip -----------------------------------------------------------------------
-// fp32 -> bf16 (round to nearest even) of `count` elements; both pointers on the device.
-hipError_t launch_store_bf16(const float* src, uint16_t* dst, size_t count, hipStream_t s);
-// Per-row partial sums for the statistics.  row_acc is [rows_total][F] fp64 on the device; the
-// rows [row0, row0+rows) of it are written from `chunk` (fp32, rows x N x F, device).
-// mean64 == nullptr: sums of values; else sums of squared deviations from mean64[f] (device).
-// The chunk holds F_src <= F features per node; feature F_src (if F_src < F) is the time-of-day
-// channel (t mod period) / period, synthesised on the fly.
-hipError_t launch_row_sums(const float* chunk, int64_t rows, int32_t N, int32_t F, int32_t F_src, int32_t period,
-                           int64_t row0, const double* mean64, double* row_acc, hipStream_t s);
+// One streaming pass over a chunk of `rows` source rows (fp32, [rows][N * F_src], device):
+//   * dst != nullptr: the resident rows [rows][N * F] are written, fp32 or bf16 (rounded to nearest
+//     even).  F_src == F - 1 (with period > 0) appends the time-of-day feature (t mod period) /
+//     period of the row to every node; otherwise F_src == F.
+//   * row_acc != nullptr: row_acc[(row0 + r) * F + f] receives, in fp64, the sum over the nodes in
+//     node order of the fp32 values of feature f of row r (mean64 == nullptr) or of their squared
+//     deviations from mean64[f] (device).  row_acc is [rows of the whole series][F] on the device.
+// row0 is the absolute index of the chunk's first row.
+hipError_t launch_ingest_rows(const float* src, int64_t rows, int32_t N, int32_t F, int32_t F_src, int32_t period,
+                              int64_t row0, void* dst, bool dst_bf16, const double* mean64, double* row_acc,
+                              hipStream_t s);
 // Algorithm 1's scalar statistic over the first n_train windows of x: weighted sum of the row sums
 // over count = n_train*P*N*F elements, written to all F entries of out64 / out32.
 hipError_t launch_reduce_rows_alg1(const double* row_acc, int32_t F, int64_t n_train, int32_t P, double count,
                                    bool take_sqrt, double* out64, float* out32, hipStream_t s);
-// Resident rows [rows, N, F] (fp32 or bf16) from a source chunk [rows, N, F_src] plus the
-// time-of-day channel.
-hipError_t launch_assemble_rows(const float* src, int64_t rows, int32_t N, int32_t F_src, int32_t F, int64_t row0,
-                                int32_t period, void* dst, bool out_bf16, hipStream_t s);
-// Reduces row_acc over all T rows in a fixed order, divides by T*N; take_sqrt selects the
+// Adds the T row sums of every feature in time order, divides by T*N; take_sqrt selects the
 // standard deviation.  out64 is [F] fp64 on the device, out32 [F] fp32 on the device.
 hipError_t launch_reduce_rows(const double* row_acc, int64_t T, int32_t N, int32_t F, bool take_sqrt,
                               double* out64, float* out32, hipStream_t s);

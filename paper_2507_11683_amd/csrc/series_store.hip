@@ -1,14 +1,36 @@
 // Resident series store (Sec. 4.1 of the paper, GPU-Index-Batching: the data is migrated to GPU
-// memory once; Eq. 2: a single copy of the data is kept).  Device-side helpers used while the
-// series is loaded: the optional fp32 -> bf16 storage rounding and the per-feature mean /
-// population standard deviation (Algorithm 1 standardises with the mean and standard deviation;
-// its caption allows other ranges than its own, here every feature over the whole series).
+// memory once and the preprocessing runs there; Eq. 2: a single copy of the data is kept).
+// Device-side work of a load, all in one streaming kernel per chunk of rows:
+//   * writing the resident rows: plain fp32, or rounded to bf16, optionally with the time-of-day
+//     feature appended to every node (stage 1 of the preprocessing);
+//   * the row sums behind the statistics (Algorithm 1 standardises with a mean and a standard
+//     deviation): per (row, feature) the fp64 sum of the values, or of the squared deviations from a
+//     given mean, taken over the nodes IN NODE ORDER, one addition after the other.  The order is
+//     part of the definition of the statistics (row by row, then the row sums in time order), so the
+//     result does not depend on the launch shape and equals a plain sequential loop bit for bit.
+//
+// How a sequential sum runs at memory speed: a workgroup owns up to 32 rows and walks them tile by
+// tile (32 rows x 256 columns).  All 256 lanes load the tile with coalesced 16-byte accesses (and
+// store it to the resident series on the way); the tile goes to LDS; then one lane per (row,
+// feature) chain adds its elements of the tile to its running fp64 sum, in order.  The next tile's
+// loads are issued before that serial phase, and several workgroups share a CU, so memory stays
+// busy while the chains advance.  105,120 rows x 2 features give 210,240 independent chains.
+// A step of a chain costs a SIMD about 48 cycles whether 2 or 64 lanes of the wave take part, so the
+// tile is as tall as the 64 KB of LDS allow with rows of 1 KB: 64 chains per serial phase keep the
+// sums (and, measured, the whole kernel: it runs as fast with the sums switched off) memory bound.
+// Wider, shorter tiles stream a little faster (8 x 1024: +6 %) but their 16 chains become the limit.
+#include <type_traits>
+
 #include "pgti_internal.h"
 
 namespace pgti {
 namespace {
 
 constexpr int kThreads = 256;
+constexpr int kTileRows = 32;
+constexpr int kTileCols = 256;
+constexpr int kTilePitchMax = kTileCols + 31;
+constexpr int kGroupFeatures = 256;  // chains of one workgroup cover at most this many features
 
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
@@ -21,93 +43,272 @@ __device__ __forceinline__ uint32_t bf16_bits(float v) {
     return (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;
 }
 
-__global__ void __launch_bounds__(kThreads) store_bf16_kernel(const float* __restrict__ src,
-                                                              uint16_t* __restrict__ dst, size_t count) {
-    const size_t quads = count / 4;
-    const size_t stride = static_cast<size_t>(gridDim.x) * kThreads;
-    for (size_t q = static_cast<size_t>(blockIdx.x) * kThreads + threadIdx.x; q < quads; q += stride) {
-        f32x4 v = reinterpret_cast<const f32x4*>(src)[q];
-        u32x2 o;
-        o.x = bf16_bits(v.x) | (bf16_bits(v.y) << 16);
-        o.y = bf16_bits(v.z) | (bf16_bits(v.w) << 16);
-        reinterpret_cast<u32x2*>(dst)[q] = o;
-    }
-    // tail of count % 4 elements
-    const size_t tail0 = quads * 4;
-    if (blockIdx.x == 0 && threadIdx.x < count - tail0)
-        dst[tail0 + threadIdx.x] = static_cast<uint16_t>(bf16_bits(src[tail0 + threadIdx.x]));
-}
-
 // Time of day of absolute timestep t: (t mod period) / period, the quotient taken in binary32.
 __device__ __forceinline__ float time_of_day(int64_t t, int32_t period) {
     return static_cast<float>(static_cast<int32_t>(t % period)) / static_cast<float>(period);
 }
 
-// Writes rows of the resident series from a source chunk with fewer features: out[t, node, f] =
-// src[t, node, f] for f < F_src, and the time-of-day value of the row for f == F_src (stage 1 of the
-// preprocessing: the same value for every node of a timestep).  One output element per thread.
-template <bool OUT_BF16>
-__global__ void __launch_bounds__(kThreads) assemble_rows_kernel(const float* __restrict__ src, int64_t rows,
-                                                                 int32_t N, int32_t F_src, int32_t F, int64_t row0,
-                                                                 int32_t period, void* __restrict__ dst) {
-    const int64_t total = rows * N * F;
-    const int64_t stride = static_cast<int64_t>(gridDim.x) * kThreads;
-    for (int64_t i = static_cast<int64_t>(blockIdx.x) * kThreads + threadIdx.x; i < total; i += stride) {
-        const int64_t cell = i / F;  // (row, node)
-        const int32_t f = static_cast<int32_t>(i - cell * F);
-        const float v = (f < F_src) ? src[cell * F_src + f] : time_of_day(row0 + cell / N, period);
-        if constexpr (OUT_BF16) static_cast<uint16_t*>(dst)[i] = static_cast<uint16_t>(bf16_bits(v));
-        else static_cast<float*>(dst)[i] = v;
-    }
-}
+struct IngestArgs {
+    const float* src;      // [rows][N * F_src] fp32
+    void* dst;             // [rows][N * F] fp32 or bf16 (dst_bf16), or null: nothing is written
+    const double* mean64;  // null: sums of values; else sums of squared deviations from mean64[f]
+    double* row_acc;       // [all rows of the series][F], or null: no sums
+    int64_t rows;          // rows of this chunk
+    int64_t row0;          // absolute index of the chunk's first row
+    int32_t N, F, F_src, period;
+    int32_t rows_blk;      // rows per workgroup: rows_blk * min(F, 256) <= 256
+    int32_t dst_bf16;
+};
 
-// One wave per (row, feature): lane l adds the nodes l, l+64, ... in node order, then the 64 lane
-// sums are combined in a fixed butterfly.  The order depends on nothing but N, so the result does
-// not depend on how the series was cut into chunks.  The chunk holds F_src features per node; a
-// feature f >= F_src is the synthesised time-of-day channel.
-__global__ void __launch_bounds__(kThreads) row_sums_kernel(const float* __restrict__ chunk, int64_t rows,
-                                                            int32_t N, int32_t F, int32_t F_src, int32_t period,
-                                                            int64_t row0, const double* __restrict__ mean64,
-                                                            double* __restrict__ row_acc) {
-    const uint32_t lane = threadIdx.x & 63u;
-    const int64_t wave = static_cast<int64_t>(blockIdx.x) * (kThreads / 64) + (threadIdx.x >> 6);
-    if (wave >= rows * F) return;  // whole waves leave together
-    const int64_t row = wave / F;
-    const int32_t f = static_cast<int32_t>(wave % F);
-    const bool synth = f >= F_src;
-    const float* p = chunk + row * static_cast<int64_t>(N) * F_src + (synth ? 0 : f);
-    const double tod = synth ? static_cast<double>(time_of_day(row0 + row, period)) : 0.0;
-    const double mu = mean64 ? mean64[f] : 0.0;
-    double acc = 0.0;
-    auto add = [&](double v) {
-        if (mean64) {
-            const double d = v - mu;
-            acc += d * d;
+// One chain's share of a tile: acc = (...((acc + t(x_j)) + t(x_{j+F})) + ...) over the elements
+// j, j+F, j+2F, ... < width of an LDS row, in that order; t(x) = x widened to fp64, or its squared
+// deviation from mu (two roundings: the subtraction and the product).  The additions are serial by
+// definition; the LDS reads of the next eight elements are issued before the current eight are
+// added.
+template <bool SQUARES>
+__device__ __forceinline__ double fold_chain(const float* __restrict__ rowp, int32_t j, int32_t width, int32_t F,
+                                             double mu, double acc) {
+    constexpr int kBurst = 8;
+    auto term = [&](float x) -> double {
+        if constexpr (SQUARES) {
+            const double d = static_cast<double>(x) - mu;
+            return d * d;
         } else {
-            acc += v;
+            return static_cast<double>(x);
         }
     };
-    if (synth) {
-        // same value for every node of the row; same additions, in the same order, as for a stored feature
-        for (int32_t node = lane; node < N; node += 64) add(tod);
-    } else {
-        // Sixteen loads are issued before the first is added (a wave has a whole row to itself, so
-        // its load latencies would otherwise run one after the other); the additions keep the node
-        // order.  The loads are unconditional inside this branch so that they can be in flight together.
-        constexpr int32_t kAhead = 16;
-        int32_t node = lane;
-        for (; node + 64 * (kAhead - 1) < N; node += 64 * kAhead) {
-            float v[kAhead];
+    const int32_t step = kBurst * F, reach = (kBurst - 1) * F;
+    if (j + reach < width) {
+        float cur[kBurst], nxt[kBurst];
 #pragma unroll
-            for (int32_t u = 0; u < kAhead; ++u) v[u] = p[static_cast<int64_t>(node + 64 * u) * F_src];
+        for (int u = 0; u < kBurst; ++u) cur[u] = rowp[j + u * F];
+        j += step;
+        while (j + reach < width) {
 #pragma unroll
-            for (int32_t u = 0; u < kAhead; ++u) add(static_cast<double>(v[u]));
+            for (int u = 0; u < kBurst; ++u) nxt[u] = rowp[j + u * F];
+#pragma unroll
+            for (int u = 0; u < kBurst; ++u) acc += term(cur[u]);
+#pragma unroll
+            for (int u = 0; u < kBurst; ++u) cur[u] = nxt[u];
+            j += step;
         }
-        for (; node < N; node += 64) add(static_cast<double>(p[static_cast<int64_t>(node) * F_src]));
-    }
 #pragma unroll
-    for (int off = 32; off >= 1; off >>= 1) acc += __shfl_xor(acc, off, 64);
-    if (lane == 0) row_acc[(row0 + row) * F + f] = acc;
+        for (int u = 0; u < kBurst; ++u) acc += term(cur[u]);
+    }
+    for (; j < width; j += F) acc += term(rowp[j]);
+    return acc;
+}
+
+// VEC4: a lane moves 16-byte quads of the OUTPUT row (rows are whole quads and the pointers are
+// aligned for them); SYNTH: F_src = F - 1 and feature F - 1 is the time of day of the row.  VEC4 with
+// SYNTH is the common case of one stored feature plus the time of day (F_src = 1, F = 2): an output
+// quad is (v0, tod, v1, tod), made from one 8-byte load.
+template <bool VEC4, bool SYNTH>
+__global__ void __launch_bounds__(kThreads) ingest_rows_kernel(IngestArgs a) {
+    __shared__ float tile[kTileRows * kTilePitchMax];
+    __shared__ float tods[kTileRows];  // time of day of the workgroup's rows (SYNTH)
+    using Reg = typename std::conditional<VEC4, f32x4, float>::type;
+    constexpr int kPasses = VEC4 ? (kTileRows * kTileCols / 4) / kThreads : kTileRows;
+
+    const uint32_t tid = threadIdx.x;
+    const int32_t F = a.F;
+    const int64_t R = static_cast<int64_t>(a.N) * F, R_src = static_cast<int64_t>(a.N) * a.F_src;
+    const int64_t r_first = static_cast<int64_t>(blockIdx.x) * a.rows_blk;  // inside the chunk
+    const int64_t rows_left = a.rows - r_first;
+    const int32_t rows_here = rows_left < a.rows_blk ? static_cast<int32_t>(rows_left) : a.rows_blk;
+    const int32_t f_lo = static_cast<int32_t>(blockIdx.y) * kGroupFeatures;
+    const int32_t Fg = (F - f_lo < kGroupFeatures) ? F - f_lo : kGroupFeatures;
+    const uint32_t pitch = kTileCols + (F & 31);  // chain c reads bank (c + const) mod 32: no conflicts
+    const bool sums = a.row_acc != nullptr;
+    const bool squares = a.mean64 != nullptr;
+    const bool writes = a.dst != nullptr && blockIdx.y == 0;
+    const bool has_chain = sums && static_cast<int32_t>(tid) < rows_here * Fg;
+    const int32_t chain_row = static_cast<int32_t>(tid) / Fg, chain_f = f_lo + static_cast<int32_t>(tid) % Fg;
+    double acc = 0.0;
+    const double mu = (has_chain && squares) ? a.mean64[chain_f] : 0.0;
+
+    // position of this lane's element(s) inside a tile: pass p takes quad p*256 + tid of the tile (VEC4)
+    // or element tid of row p
+    auto pass_row = [&](int p) -> int32_t {
+        return VEC4 ? static_cast<int32_t>((p * kThreads + tid) / (kTileCols / 4)) : p;
+    };
+    auto pass_col = [&](int p) -> int32_t {
+        return VEC4 ? 4 * static_cast<int32_t>((p * kThreads + tid) % (kTileCols / 4)) : static_cast<int32_t>(tid);
+    };
+
+    if constexpr (SYNTH) {
+        if (tid < kTileRows) tods[tid] = time_of_day(a.row0 + r_first + tid, a.period);
+        __syncthreads();
+    }
+
+    Reg regs[kPasses];
+    auto load_tile = [&](int64_t c0) {
+#pragma unroll
+        for (int p = 0; p < kPasses; ++p) {
+            const int32_t rr = pass_row(p), lane_col = pass_col(p);
+            const int64_t col = c0 + lane_col;
+            const bool valid = rr < rows_here && col < R;
+            if constexpr (VEC4 && SYNTH) {
+                regs[p] = f32x4{0.f, 0.f, 0.f, 0.f};
+                if (valid) {
+                    const u32x2* sp = reinterpret_cast<const u32x2*>(a.src + (r_first + rr) * R_src + (col >> 1));
+                    const u32x2 v = __builtin_nontemporal_load(sp);
+                    const float tod = tods[rr];
+                    regs[p] = f32x4{__uint_as_float(v.x), tod, __uint_as_float(v.y), tod};
+                }
+            } else if constexpr (VEC4) {
+                regs[p] = f32x4{0.f, 0.f, 0.f, 0.f};
+                if (valid) {
+                    const f32x4* sp = reinterpret_cast<const f32x4*>(a.src + (r_first + rr) * R + col);
+                    regs[p] = __builtin_nontemporal_load(sp);  // every byte is used once
+                }
+            } else if constexpr (SYNTH) {
+                regs[p] = 0.f;
+                if (valid) {
+                    const int32_t node = static_cast<int32_t>(col) / F, f = static_cast<int32_t>(col) - node * F;
+                    regs[p] = (f < a.F_src) ? a.src[(r_first + rr) * R_src + static_cast<int64_t>(node) * a.F_src + f]
+                                            : tods[rr];
+                }
+            } else {
+                regs[p] = 0.f;
+                if (valid) regs[p] = a.src[(r_first + rr) * R + col];
+            }
+        }
+    };
+
+    load_tile(0);
+    for (int64_t c0 = 0; c0 < R; c0 += kTileCols) {
+        // registers -> resident series, registers -> LDS
+#pragma unroll
+        for (int p = 0; p < kPasses; ++p) {
+            const int32_t rr = pass_row(p), lane_col = pass_col(p);
+            const int64_t col = c0 + lane_col;
+            const bool valid = rr < rows_here && col < R;
+            if (writes && valid) {
+                const int64_t at = (r_first + rr) * R + col;
+                if constexpr (VEC4) {
+                    if (a.dst_bf16) {
+                        u32x2 o;
+                        o.x = bf16_bits(regs[p].x) | (bf16_bits(regs[p].y) << 16);
+                        o.y = bf16_bits(regs[p].z) | (bf16_bits(regs[p].w) << 16);
+                        u32x2* dp = reinterpret_cast<u32x2*>(static_cast<uint16_t*>(a.dst) + at);
+                        __builtin_nontemporal_store(o, dp);
+                    } else {
+                        f32x4* dp = reinterpret_cast<f32x4*>(static_cast<float*>(a.dst) + at);
+                        __builtin_nontemporal_store(regs[p], dp);
+                    }
+                } else {
+                    if (a.dst_bf16) static_cast<uint16_t*>(a.dst)[at] = static_cast<uint16_t>(bf16_bits(regs[p]));
+                    else static_cast<float*>(a.dst)[at] = regs[p];
+                }
+            }
+            if (sums) {
+                float* t = tile + rr * pitch + lane_col;
+                if constexpr (VEC4) {
+                    t[0] = regs[p].x;
+                    t[1] = regs[p].y;
+                    t[2] = regs[p].z;
+                    t[3] = regs[p].w;
+                } else {
+                    t[0] = regs[p];
+                }
+            }
+        }
+        if (!sums) {
+            if (c0 + kTileCols < R) load_tile(c0 + kTileCols);
+            continue;
+        }
+        __syncthreads();
+        if (c0 + kTileCols < R) load_tile(c0 + kTileCols);  // in flight during the serial phase
+        if (has_chain) {
+            const int32_t width = (R - c0 < kTileCols) ? static_cast<int32_t>(R - c0) : kTileCols;
+            const int32_t phase = static_cast<int32_t>(c0) % F;
+            int32_t j = chain_f - phase;  // first column of the tile that holds feature chain_f
+            if (j < 0) j += F;
+            const float* rowp = tile + chain_row * pitch;
+            acc = squares ? fold_chain<true>(rowp, j, width, F, mu, acc) : fold_chain<false>(rowp, j, width, F, mu, acc);
+        }
+        __syncthreads();
+    }
+    if (has_chain) a.row_acc[(a.row0 + r_first + chain_row) * F + chain_f] = acc;
+}
+
+// The row sums in time order: thread f of workgroup b adds row_acc[t][256 b + f] for t = 0, 1, ...
+// T-1, one after the other (the order is part of the definition).  All lanes stage the table through
+// LDS, 2,048 entries at a time and transposed, so that every chain finds its values side by side; the
+// next chunk's loads are in flight while the chains advance, and a chain fetches its next sixteen values
+// from LDS while it adds the current sixteen, so that only the additions themselves are serial.
+// result = total / count, optionally square-rooted; out64 keeps it for the next sweep.
+constexpr int kReduceChunk = 2048;
+
+__global__ void __launch_bounds__(kThreads) reduce_rows_seq_kernel(const double* __restrict__ row_acc, int64_t T,
+                                                                   int32_t F, double count, int take_sqrt,
+                                                                   double* __restrict__ out64,
+                                                                   float* __restrict__ out32) {
+    __shared__ double buf[kReduceChunk];
+    constexpr int kPer = kReduceChunk / kThreads;
+    constexpr int kBurst = 16;
+    const int32_t tid = threadIdx.x;
+    const int32_t f0 = static_cast<int32_t>(blockIdx.x) * kGroupFeatures;
+    const int32_t Fb = (F - f0 < kGroupFeatures) ? F - f0 : kGroupFeatures;
+    const int32_t rows_chunk = kReduceChunk / Fb;  // >= 8
+    double regs[kPer];
+    auto load_chunk = [&](int64_t t0) {
+        const int64_t rows = (T - t0 < rows_chunk) ? T - t0 : rows_chunk;
+#pragma unroll
+        for (int p = 0; p < kPer; ++p) {
+            const int32_t idx = tid + p * kThreads;
+            const int32_t r = idx / Fb, fl = idx - r * Fb;
+            regs[p] = (r < rows) ? row_acc[(t0 + r) * F + f0 + fl] : 0.0;
+        }
+    };
+    double total = 0.0;
+    load_chunk(0);
+    for (int64_t t0 = 0; t0 < T; t0 += rows_chunk) {
+#pragma unroll
+        for (int p = 0; p < kPer; ++p) {
+            const int32_t idx = tid + p * kThreads;
+            const int32_t r = idx / Fb, fl = idx - r * Fb;
+            if (r < rows_chunk) buf[fl * rows_chunk + r] = regs[p];
+        }
+        __syncthreads();
+        if (t0 + rows_chunk < T) load_chunk(t0 + rows_chunk);
+        if (tid < Fb) {
+            const int32_t rows = static_cast<int32_t>((T - t0 < rows_chunk) ? T - t0 : rows_chunk);
+            const double* mine = buf + tid * rows_chunk;
+            // two register buffers take turns: while one burst is added, the next is on its way from LDS
+            double va[kBurst], vb[kBurst];
+            auto fetch = [&](double (&v)[kBurst], int32_t at) {
+#pragma unroll
+                for (int u = 0; u < kBurst; ++u) v[u] = mine[at + u];
+            };
+            auto add_all = [&](const double (&v)[kBurst]) {
+#pragma unroll
+                for (int u = 0; u < kBurst; ++u) total += v[u];
+            };
+            int32_t r = 0;
+            if (rows >= kBurst) {
+                fetch(va, 0);
+                r = kBurst;
+                while (r + 2 * kBurst <= rows) {
+                    fetch(vb, r);
+                    add_all(va);
+                    fetch(va, r + kBurst);
+                    add_all(vb);
+                    r += 2 * kBurst;
+                }
+                add_all(va);
+            }
+            for (; r < rows; ++r) total += mine[r];
+        }
+        __syncthreads();
+    }
+    if (tid < Fb) {
+        double r = total / count;
+        if (take_sqrt) r = sqrt(r);
+        out64[f0 + tid] = r;
+        out32[f0 + tid] = static_cast<float>(r);
+    }
 }
 
 // Algorithm 1's statistics: one scalar over every element of x_train, the first n_train windows of
@@ -163,67 +364,48 @@ __global__ void __launch_bounds__(kThreads) reduce_rows_alg1_kernel(const double
     }
 }
 
-// One workgroup per feature: thread i adds the rows i, i+256, ... in time order, then a fixed
-// LDS tree; result / (T*N), optionally square-rooted.
-__global__ void __launch_bounds__(kThreads) reduce_rows_kernel(const double* __restrict__ row_acc, int64_t T,
-                                                               int32_t N, int32_t F, int take_sqrt,
-                                                               double* __restrict__ out64,
-                                                               float* __restrict__ out32) {
-    __shared__ double part[kThreads];
-    const int32_t f = blockIdx.x;
-    double acc = 0.0;
-    // rows are read eight ahead (one workgroup walks a whole column); the additions keep the row order
-    constexpr int kAhead = 8;
-    int64_t t = threadIdx.x;
-    for (; t + static_cast<int64_t>(kThreads) * (kAhead - 1) < T; t += static_cast<int64_t>(kThreads) * kAhead) {
-        double v[kAhead];
-#pragma unroll
-        for (int u = 0; u < kAhead; ++u) v[u] = row_acc[(t + static_cast<int64_t>(kThreads) * u) * F + f];
-#pragma unroll
-        for (int u = 0; u < kAhead; ++u) acc += v[u];
-    }
-    for (; t < T; t += kThreads) acc += row_acc[t * F + f];
-    part[threadIdx.x] = acc;
-    __syncthreads();
-    for (uint32_t off = kThreads / 2; off >= 1; off >>= 1) {
-        if (threadIdx.x < off) part[threadIdx.x] += part[threadIdx.x + off];
-        __syncthreads();
-    }
-    if (threadIdx.x == 0) {
-        double r = part[0] / (static_cast<double>(T) * static_cast<double>(N));
-        if (take_sqrt) r = sqrt(r);
-        out64[f] = r;
-        out32[f] = static_cast<float>(r);
-    }
-}
-
 }  // namespace
 
-hipError_t launch_store_bf16(const float* src, uint16_t* dst, size_t count, hipStream_t s) {
-    if (count == 0) return hipSuccess;
-    size_t quads = count / 4;
-    size_t want = (quads + kThreads - 1) / kThreads;
-    uint32_t grid = static_cast<uint32_t>(want < 1 ? 1 : (want > 16384 ? 16384 : want));
-    hipLaunchKernelGGL(store_bf16_kernel, dim3(grid), dim3(kThreads), 0, s, src, dst, count);
-    return hipGetLastError();
-}
-
-hipError_t launch_row_sums(const float* chunk, int64_t rows, int32_t N, int32_t F, int32_t F_src, int32_t period,
-                           int64_t row0, const double* mean64, double* row_acc, hipStream_t s) {
-    if (rows <= 0) return hipSuccess;
-    const int64_t waves = rows * F;
-    const int64_t per_block = kThreads / 64;
-    const int64_t grid = (waves + per_block - 1) / per_block;
-    if (grid > 0x7FFFFFFF) return hipErrorInvalidValue;
-    hipLaunchKernelGGL(row_sums_kernel, dim3(static_cast<uint32_t>(grid)), dim3(kThreads), 0, s, chunk, rows,
-                       N, F, F_src, period, row0, mean64, row_acc);
+hipError_t launch_ingest_rows(const float* src, int64_t rows, int32_t N, int32_t F, int32_t F_src, int32_t period,
+                              int64_t row0, void* dst, bool dst_bf16, const double* mean64, double* row_acc,
+                              hipStream_t s) {
+    if (rows <= 0 || (!dst && !row_acc)) return hipSuccess;
+    if (F_src != F && (F_src != F - 1 || period <= 0)) return hipErrorInvalidValue;
+    IngestArgs a{};
+    a.src = src;
+    a.dst = dst;
+    a.mean64 = mean64;
+    a.row_acc = row_acc;
+    a.rows = rows;
+    a.row0 = row0;
+    a.N = N;
+    a.F = F;
+    a.F_src = F_src;
+    a.period = period;
+    a.dst_bf16 = dst_bf16 ? 1 : 0;
+    const int32_t Fg = F < kGroupFeatures ? F : kGroupFeatures;
+    a.rows_blk = kThreads / Fg < kTileRows ? kThreads / Fg : kTileRows;
+    const int64_t blocks = (rows + a.rows_blk - 1) / a.rows_blk;
+    const int64_t groups = row_acc ? (F + kGroupFeatures - 1) / kGroupFeatures : 1;
+    if (blocks > 0x7FFFFFFF || groups > 65535) return hipErrorInvalidValue;
+    const dim3 grid(static_cast<uint32_t>(blocks), static_cast<uint32_t>(groups)), block(kThreads);
+    const int64_t R = static_cast<int64_t>(N) * F;
+    const bool synth = F_src != F;
+    const uintptr_t dst_align = dst ? reinterpret_cast<uintptr_t>(dst) & (dst_bf16 ? 7u : 15u) : 0u;
+    const bool vec4 = !synth && R % 4 == 0 && (reinterpret_cast<uintptr_t>(src) & 15u) == 0 && dst_align == 0;
+    const bool synth_pairs = synth && F == 2 && N % 2 == 0 && (reinterpret_cast<uintptr_t>(src) & 7u) == 0 && dst_align == 0;
+    if (synth_pairs) hipLaunchKernelGGL((ingest_rows_kernel<true, true>), grid, block, 0, s, a);
+    else if (synth) hipLaunchKernelGGL((ingest_rows_kernel<false, true>), grid, block, 0, s, a);
+    else if (vec4) hipLaunchKernelGGL((ingest_rows_kernel<true, false>), grid, block, 0, s, a);
+    else hipLaunchKernelGGL((ingest_rows_kernel<false, false>), grid, block, 0, s, a);
     return hipGetLastError();
 }
 
 hipError_t launch_reduce_rows(const double* row_acc, int64_t T, int32_t N, int32_t F, bool take_sqrt,
                               double* out64, float* out32, hipStream_t s) {
-    hipLaunchKernelGGL(reduce_rows_kernel, dim3(F), dim3(kThreads), 0, s, row_acc, T, N, F,
-                       take_sqrt ? 1 : 0, out64, out32);
+    const uint32_t blocks = static_cast<uint32_t>((F + kGroupFeatures - 1) / kGroupFeatures);
+    hipLaunchKernelGGL(reduce_rows_seq_kernel, dim3(blocks), dim3(kThreads), 0, s, row_acc, T, F,
+                       static_cast<double>(T) * static_cast<double>(N), take_sqrt ? 1 : 0, out64, out32);
     return hipGetLastError();
 }
 
@@ -231,21 +413,6 @@ hipError_t launch_reduce_rows_alg1(const double* row_acc, int32_t F, int64_t n_t
                                    bool take_sqrt, double* out64, float* out32, hipStream_t s) {
     hipLaunchKernelGGL(reduce_rows_alg1_kernel, dim3(1), dim3(kThreads), 0, s, row_acc, F, n_train, P, count,
                        take_sqrt ? 1 : 0, out64, out32);
-    return hipGetLastError();
-}
-
-hipError_t launch_assemble_rows(const float* src, int64_t rows, int32_t N, int32_t F_src, int32_t F, int64_t row0,
-                                int32_t period, void* dst, bool out_bf16, hipStream_t s) {
-    if (rows <= 0) return hipSuccess;
-    const int64_t total = rows * N * F;
-    const int64_t want = (total + kThreads - 1) / kThreads;
-    const uint32_t grid = static_cast<uint32_t>(want > 65536 ? 65536 : want);
-    if (out_bf16)
-        hipLaunchKernelGGL(assemble_rows_kernel<true>, dim3(grid), dim3(kThreads), 0, s, src, rows, N, F_src, F, row0,
-                           period, dst);
-    else
-        hipLaunchKernelGGL(assemble_rows_kernel<false>, dim3(grid), dim3(kThreads), 0, s, src, rows, N, F_src, F, row0,
-                           period, dst);
     return hipGetLastError();
 }
 
