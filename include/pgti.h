@@ -46,11 +46,19 @@ typedef enum {
     PGTI_ERR_HIP = -6    /* any other HIP runtime error (text in pgti_last_error) */
 } pgti_status;
 
-/* Creates a context on GPU `device` (ordinal as seen by HIP).  *out receives the handle.
- * Reads the environment variable PGTI_SORT_BUCKET_CAP once, here: a test hook that lowers the
- * size (1..2047) up to which the epoch sort orders a bucket in on-chip memory, so that the slow
- * ordering path for oversized buckets can be exercised; results do not depend on it. */
+/* Creates a context on GPU `device` (ordinal as seen by HIP).  *out receives the handle. */
 int pgti_create(pgti_ctx** out, int device);
+
+/* Test hook for the epoch sort of this context (no effect on any other state; not for production).
+ * bucket_cap: 0 = default; 1..2047 lowers the size up to which a bucket of keys is ordered in
+ *     on-chip memory, so that the slow ordering path for oversized buckets runs; results do not
+ *     depend on it.
+ * key_bits: 0 or 64 = the full 64-bit keys (the distinct keys of Sec. 4.2's shuffle as defined at
+ *     pgti_epoch_indices); 1..63 keeps only the top key_bits bits of every key, so that many starts
+ *     share a key and the order among them is decided by the index alone (lower start first).
+ *     This changes the epoch order: it exists to exercise the tie-break, which full keys never do.
+ * Returns PGTI_OK or PGTI_ERR_ARG.  Takes effect at the next index generation. */
+int pgti_set_sort_test_hooks(pgti_ctx* c, uint32_t bucket_cap, uint32_t key_bits);
 
 /* Frees everything the context owns after waiting for the device work it enqueued on its own
  * stream and for the streams that received batch builds since the last epoch-index generation.

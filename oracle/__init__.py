@@ -54,6 +54,8 @@ def _load():
         lib.oracle_splitmix64_next.argtypes = [ctypes.POINTER(u64)]
         lib.oracle_key.restype = u64
         lib.oracle_key.argtypes = [u64, u64, u64]
+        lib.oracle_keys.restype = ctypes.c_int
+        lib.oracle_keys.argtypes = [u64, u64, i64, vp]
         lib.oracle_sort_pairs.restype = ctypes.c_int
         lib.oracle_sort_pairs.argtypes = [vp, i64, vp]
         lib.oracle_epoch_perm.restype = ctypes.c_int
@@ -136,6 +138,13 @@ def splitmix64_stream(state: int, count: int) -> list[int]:
 
 def key(seed: int, epoch: int, i: int) -> int:
     return int(_load().oracle_key(seed, epoch, i))
+
+
+def keys(seed: int, epoch: int, n: int) -> np.ndarray:
+    """key(seed, epoch, i) for i = 0 .. n-1."""
+    out = np.empty(max(n, 0), dtype=np.uint64)
+    _check(_load().oracle_keys(seed, epoch, n, _ptr(out)), "keys")
+    return out
 
 
 def sort_pairs(keys: np.ndarray) -> np.ndarray:

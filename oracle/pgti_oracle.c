@@ -89,6 +89,14 @@ uint64_t oracle_key(uint64_t seed, uint64_t epoch, uint64_t i) {
     return oracle_mix64((h1 ^ i) + g);
 }
 
+/* The keys of the first n starts of an epoch, keys_out[i] = key(seed, epoch, i): the list that
+ * oracle_sort_pairs orders into the epoch's permutation. */
+int oracle_keys(uint64_t seed, uint64_t epoch, int64_t n, uint64_t* keys_out) {
+    if (n < 0 || (n > 0 && !keys_out)) return ORACLE_ERR_ARG;
+    for (int64_t i = 0; i < n; ++i) keys_out[i] = oracle_key(seed, epoch, (uint64_t)i);
+    return ORACLE_OK;
+}
+
 typedef struct {
     uint64_t key;
     int32_t idx;

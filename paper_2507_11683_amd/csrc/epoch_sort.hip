@@ -71,8 +71,8 @@ __device__ __forceinline__ uint32_t block_inclusive_scan(uint32_t v, uint32_t* l
 // per (digit, workgroup) into hist0[digit][wg].
 __global__ void __launch_bounds__(kThreads) keygen_kernel(uint64_t seed, uint64_t epoch, uint32_t n,
                                                           uint32_t nblk, uint64_t counter_base,
-                                                          uint64_t counter_stride, uint64_t* keys,
-                                                          uint32_t* hist0) {
+                                                          uint64_t counter_stride, uint64_t key_mask,
+                                                          uint64_t* keys, uint32_t* hist0) {
     __shared__ uint32_t counts[kRadix];
     const uint32_t tid = threadIdx.x, b = blockIdx.x;
     counts[tid] = 0;
@@ -83,7 +83,7 @@ __global__ void __launch_bounds__(kThreads) keygen_kernel(uint64_t seed, uint64_
     for (uint32_t it = 0; it < kItems; ++it) {
         uint32_t i = b * kSortTile + it * kThreads + tid;
         if (i < n) {
-            uint64_t k = mix64((h1 ^ (counter_base + static_cast<uint64_t>(i) * counter_stride)) + kGamma);
+            uint64_t k = mix64((h1 ^ (counter_base + static_cast<uint64_t>(i) * counter_stride)) + kGamma) & key_mask;
             keys[i] = k;
             atomicAdd(&counts[k & 0xFFu], 1u);
         }
@@ -218,7 +218,7 @@ constexpr uint32_t kSmallSortThreads = 512;
 
 __global__ void __launch_bounds__(kSmallSortThreads) small_sort_kernel(uint64_t seed, uint64_t epoch, uint32_t n,
                                                                         uint32_t m, uint64_t counter_base,
-                                                                        uint64_t counter_stride,
+                                                                        uint64_t counter_stride, uint64_t key_mask,
                                                                         int32_t* __restrict__ share, uint32_t lo,
                                                                         uint32_t hi, int32_t value_offset) {
     __shared__ uint64_t key[kSmallSortKeys];
@@ -227,7 +227,7 @@ __global__ void __launch_bounds__(kSmallSortThreads) small_sort_kernel(uint64_t 
     const uint64_t h0 = mix64(seed + kGamma);
     const uint64_t h1 = mix64((h0 ^ epoch) + kGamma);
     for (uint32_t i = tid; i < m; i += kSmallSortThreads) {
-        key[i] = (i < n) ? mix64((h1 ^ (counter_base + i * counter_stride)) + kGamma) : ~0ull;
+        key[i] = (i < n) ? (mix64((h1 ^ (counter_base + i * counter_stride)) + kGamma) & key_mask) : ~0ull;
         idx[i] = i;
     }
     __syncthreads();
@@ -258,11 +258,14 @@ __global__ void __launch_bounds__(kSmallSortThreads) small_sort_kernel(uint64_t 
 constexpr uint32_t kBucketBins = kMaxSortBuckets / kThreads;  // bins per thread in the offset scan: 4
 static_assert(kBucketBins * kThreads == kMaxSortBuckets, "whole bins per thread");
 
-__device__ __forceinline__ uint64_t epoch_key(uint64_t h1, uint64_t counter) { return mix64((h1 ^ counter) + kGamma); }
+__device__ __forceinline__ uint64_t epoch_key(uint64_t h1, uint64_t counter, uint64_t key_mask) {
+    return mix64((h1 ^ counter) + kGamma) & key_mask;
+}
 
 __global__ void __launch_bounds__(kThreads) bucket_count_kernel(uint64_t seed, uint64_t epoch, uint32_t n,
                                                                 uint64_t counter_base, uint64_t counter_stride,
-                                                                uint32_t dbits, uint32_t* __restrict__ tot) {
+                                                                uint64_t key_mask, uint32_t dbits,
+                                                                uint32_t* __restrict__ tot) {
     __shared__ uint32_t hist[kMaxSortBuckets];
     const uint32_t tid = threadIdx.x, D = 1u << dbits;
     for (uint32_t bin = tid; bin < D; bin += kThreads) hist[bin] = 0;
@@ -271,7 +274,7 @@ __global__ void __launch_bounds__(kThreads) bucket_count_kernel(uint64_t seed, u
 #pragma unroll
     for (uint32_t it = 0; it < kItems; ++it) {
         const uint32_t i = blockIdx.x * kSortTile + it * kThreads + tid;
-        if (i < n) atomicAdd(&hist[epoch_key(h1, counter_base + i * counter_stride) >> (64 - dbits)], 1u);
+        if (i < n) atomicAdd(&hist[epoch_key(h1, counter_base + i * counter_stride, key_mask) >> (64 - dbits)], 1u);
     }
     __syncthreads();
     for (uint32_t bin = tid; bin < D; bin += kThreads) {
@@ -285,7 +288,8 @@ __global__ void __launch_bounds__(kThreads) bucket_count_kernel(uint64_t seed, u
 // workgroup; workgroup 0 also stores it, with off[D] = n, for the next kernel).
 __global__ void __launch_bounds__(kThreads) bucket_scatter_kernel(uint64_t seed, uint64_t epoch, uint32_t n,
                                                                   uint64_t counter_base, uint64_t counter_stride,
-                                                                  uint32_t dbits, const uint32_t* __restrict__ tot,
+                                                                  uint64_t key_mask, uint32_t dbits,
+                                                                  const uint32_t* __restrict__ tot,
                                                                   uint32_t* __restrict__ cursor,
                                                                   uint32_t* __restrict__ off,
                                                                   uint64_t* __restrict__ keys_out,
@@ -302,7 +306,7 @@ __global__ void __launch_bounds__(kThreads) bucket_scatter_kernel(uint64_t seed,
 #pragma unroll
     for (uint32_t it = 0; it < kItems; ++it) {
         const uint32_t i = blockIdx.x * kSortTile + it * kThreads + tid;
-        key[it] = epoch_key(h1, counter_base + i * counter_stride);
+        key[it] = epoch_key(h1, counter_base + i * counter_stride, key_mask);
         rank[it] = (i < n) ? atomicAdd(&hist[key[it] >> (64 - dbits)], 1u) : 0u;
     }
     // offsets of the buckets: thread tid owns bins [4 tid, 4 tid + 4)
@@ -452,7 +456,7 @@ hipError_t launch_sorted_order(const SortWorkspace& w, uint64_t seed, uint64_t e
         uint32_t m = 1;
         while (m < n) m <<= 1;
         hipLaunchKernelGGL(small_sort_kernel, dim3(1), dim3(kSmallSortThreads), 0, s, seed, epoch, n, m,
-                           plan.counter_base, plan.counter_stride, plan.out, plan.out_lo, plan.out_hi,
+                           plan.counter_base, plan.counter_stride, c->key_mask, plan.out, plan.out_lo, plan.out_hi,
                            plan.value_offset);
         return hipGetLastError();
     }
@@ -466,15 +470,15 @@ hipError_t launch_sorted_order(const SortWorkspace& w, uint64_t seed, uint64_t e
         uint32_t* cursor = c->bucket + kMaxSortBuckets;
         uint32_t* off = c->bucket + 2 * kMaxSortBuckets;
         hipLaunchKernelGGL(bucket_count_kernel, dim3(nblk), dim3(kThreads), 0, s, seed, epoch, n, plan.counter_base,
-                           plan.counter_stride, dbits, tot);
+                           plan.counter_stride, c->key_mask, dbits, tot);
         hipLaunchKernelGGL(bucket_scatter_kernel, dim3(nblk), dim3(kThreads), 0, s, seed, epoch, n, plan.counter_base,
-                           plan.counter_stride, dbits, tot, cursor, off, c->keys[1], c->vals[1]);
+                           plan.counter_stride, c->key_mask, dbits, tot, cursor, off, c->keys[1], c->vals[1]);
         hipLaunchKernelGGL(bucket_sort_kernel, dim3(D), dim3(kThreads), 0, s, c->keys[1], c->vals[1], off, tot,
                            cursor, n, c->bucket_sort_cap, plan.out, plan.out_lo, plan.out_hi, plan.value_offset);
         return hipGetLastError();
     }
     hipLaunchKernelGGL(keygen_kernel, dim3(nblk), dim3(kThreads), 0, s, seed, epoch, n, nblk, plan.counter_base,
-                       plan.counter_stride, c->keys[0], c->hist[0]);
+                       plan.counter_stride, c->key_mask, c->keys[0], c->hist[0]);
     for (uint32_t pass = 0; pass < 8; ++pass) {
         uint32_t* hist = c->hist[pass & 1];
         uint32_t* hist_next = c->hist[(pass + 1) & 1];
@@ -585,6 +589,7 @@ extern "C" int64_t pgti_epoch_indices_static(int device, int64_t n_windows, uint
     w.vals[1] = reinterpret_cast<int32_t*>(p + kStaticKeysBytes);
     w.bucket = reinterpret_cast<uint32_t*>(p + kStaticKeysBytes + kStaticValsBytes);
     w.bucket_sort_cap = kBucketSortKeys;
+    w.key_mask = ~0ull;
     hipStream_t s = static_cast<hipStream_t>(stream);
     // The array keeps whatever the last call left (also a call that was cut short): totals and
     // cursors must start at zero.

@@ -140,7 +140,7 @@ int check_geometry(int64_t T, int32_t N, int32_t F, int32_t P, int32_t Q, int32_
 
 SortWorkspace workspace_of(const pgti_ctx* c) {
     return SortWorkspace{{c->d_keys[0], c->d_keys[1]}, {c->d_vals[0], c->d_vals[1]}, {c->d_hist[0], c->d_hist[1]},
-                         c->d_tot, c->d_bucket, c->bucket_sort_cap};
+                         c->d_tot, c->d_bucket, c->bucket_sort_cap, c->sort_key_mask};
 }
 
 int check_stats(const float* mean, const float* stdev, int32_t F) {
@@ -429,12 +429,7 @@ int pgti_create(pgti_ctx** out, int device) {
     pgti_ctx* c = new (std::nothrow) pgti_ctx();
     if (!c) return fail(PGTI_ERR_OOM, "host allocation failed");
     c->device = device;
-    // Test hook: a smaller limit sends buckets through the slow ordering path of the epoch sort.
     c->bucket_sort_cap = kBucketSortKeys;
-    if (const char* v = getenv("PGTI_SORT_BUCKET_CAP")) {
-        const long cap = strtol(v, nullptr, 10);
-        if (cap >= 1 && cap < static_cast<long>(kBucketSortKeys)) c->bucket_sort_cap = static_cast<uint32_t>(cap);
-    }
     DeviceGuard guard(device);
     hipError_t e = guard.status;
     // Set-up of the allocation-free epoch order: resolve this device's copy of its scratch array now,
@@ -509,6 +504,16 @@ int pgti_load_series_device(pgti_ctx* c, const float* device_series, int64_t T, 
 int pgti_load_series_ex(pgti_ctx* c, const float* series, const pgti_load_spec* spec) {
     g_error[0] = 0;
     return load_impl(c, series, spec);
+}
+
+int pgti_set_sort_test_hooks(pgti_ctx* c, uint32_t bucket_cap, uint32_t key_bits) {
+    g_error[0] = 0;
+    if (!c) return fail(PGTI_ERR_ARG, "null context");
+    if (bucket_cap >= kBucketSortKeys) return fail(PGTI_ERR_ARG, "bucket_cap %u not in [0, %u)", bucket_cap, kBucketSortKeys);
+    if (key_bits > 64) return fail(PGTI_ERR_ARG, "key_bits %u not in [0, 64]", key_bits);
+    c->bucket_sort_cap = bucket_cap ? bucket_cap : kBucketSortKeys;
+    c->sort_key_mask = (key_bits == 0 || key_bits == 64) ? ~0ull : ~((1ull << (64 - key_bits)) - 1ull);
+    return PGTI_OK;
 }
 
 int pgti_get_stats(pgti_ctx* c, float* mean_out, float* std_out) {

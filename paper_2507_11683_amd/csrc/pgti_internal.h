@@ -58,6 +58,7 @@ struct pgti_ctx {
     uint32_t* d_tot = nullptr;                 // [256] digit totals of the current pass (radix path)
     uint32_t* d_bucket = nullptr;              // bucket path: totals, cursors, offsets (see kSortBucketWords)
     uint32_t bucket_sort_cap = 0;              // largest bucket that is ordered in LDS
+    uint64_t sort_key_mask = ~0ull;            // all ones; a test hook clears low bits to force equal keys
     int32_t* d_share = nullptr;                // this rank's starts, capacity n_windows (what the builds read)
     int32_t* d_share_next = nullptr;           // where the next order is computed while builds still read d_share
     uint32_t sort_blocks = 0;
@@ -131,6 +132,7 @@ struct SortWorkspace {
     uint32_t* tot;            // [256] digit totals of the current pass (radix path)
     uint32_t* bucket;         // kSortBucketWords words (bucket path)
     uint32_t bucket_sort_cap; // largest bucket that is ordered in LDS
+    uint64_t key_mask;        // ANDed onto every key: all ones, except under the test hook that forces ties
 };
 hipError_t launch_sorted_order(const SortWorkspace& w, uint64_t seed, uint64_t epoch, const SortPlan& plan,
                                hipStream_t s);

@@ -28,6 +28,7 @@ _vp, _i64, _i32, _u64, _u32 = (ctypes.c_void_p, ctypes.c_int64, ctypes.c_int32, 
 SIGNATURES = {
     "pgti_create": (ctypes.c_int, [ctypes.POINTER(_vp), ctypes.c_int]),
     "pgti_destroy": (None, [_vp]),
+    "pgti_set_sort_test_hooks": (ctypes.c_int, [_vp, _u32, _u32]),
     "pgti_load_series": (ctypes.c_int, [_vp, _vp, _i64, _i32, _i32, _i32, _i32, _i32, ctypes.c_int, _vp, _vp]),
     "pgti_load_series_device": (ctypes.c_int, [_vp, _vp, _i64, _i32, _i32, _i32, _i32, _i32, ctypes.c_int, _vp, _vp]),
     "pgti_get_stats": (ctypes.c_int, [_vp, _vp, _vp]),
@@ -144,6 +145,10 @@ class Context:
 
     def __exit__(self, *exc):
         self.destroy()
+
+    # -- pgti_set_sort_test_hooks ------------------------------------------------------------------
+    def set_sort_test_hooks(self, bucket_cap: int = 0, key_bits: int = 0) -> None:
+        _check(self._lib.pgti_set_sort_test_hooks(self._h, bucket_cap, key_bits))
 
     # -- pgti_load_series / pgti_load_series_device ----------------------------------------------
     def load_series(self, series, P: int, Q: int, B: int, storage: int = PGTI_F32, mean=None,

@@ -370,14 +370,14 @@ def test_epoch_order_sizes(n):
         assert np.array_equal(np.concatenate(pieces), oracle.epoch_perm(3, 1, n))
 
 
-def test_epoch_order_with_oversized_buckets(monkeypatch):
+def test_epoch_order_with_oversized_buckets():
     # The bucket path orders a bucket in LDS up to a size limit and counts ranks the slow way above
     # it.  Hash keys never fill a bucket that far, so the limit is lowered for this context: with 200
     # about half of the buckets of n = 105,097 (512 buckets of about 205) take the slow way.
-    monkeypatch.setenv("PGTI_SORT_BUCKET_CAP", "200")
     n, P, Q = 105097, 1, 1
     series = np.zeros((n + P + Q - 1, 1, 1), np.float32)
     with pgti.Context(0) as ctx:
+        ctx.set_sort_test_hooks(bucket_cap=200)
         ctx.load_series(series, P, Q, 4, pgti.PGTI_F32, [0.0], [1.0])
         for seed, epoch in [(0, 0), (77, 5)]:
             assert ctx.epoch_indices(seed, epoch) == n
@@ -385,9 +385,41 @@ def test_epoch_order_with_oversized_buckets(monkeypatch):
         ctx.epoch_indices(3, 1, 2, 5)
         lo, hi = oracle.rank_share(n, 2, 5)
         assert np.array_equal(ctx.get_indices(), oracle.epoch_perm(3, 1, n)[lo:hi])
-    monkeypatch.delenv("PGTI_SORT_BUCKET_CAP")
-    with pgti.Context(0) as ctx:  # and the limit is per context: back to the default here
+        ctx.set_sort_test_hooks()  # back to the default
+        ctx.epoch_indices(0, 0)
+        assert np.array_equal(ctx.get_indices(), oracle.epoch_perm(0, 0, n))
+    with pgti.Context(0) as ctx:  # and the limit is per context
         ctx.load_series(series, P, Q, 4, pgti.PGTI_F32, [0.0], [1.0])
+        ctx.epoch_indices(0, 0)
+        assert np.array_equal(ctx.get_indices(), oracle.epoch_perm(0, 0, n))
+
+
+@pytest.mark.parametrize("n,key_bits", [(700, 4), (1024, 1), (1977, 4), (30000, 4), (105097, 4), (105097, 9),
+                                        (1100003, 4), (1100003, 12)])
+def test_equal_keys_are_ordered_by_index(n, key_bits):
+    # The full 64-bit keys of distinct starts never collide, so the index half of the (key, index)
+    # order is never decisive in an ordinary epoch.  Here the keys are cut to their top few bits
+    # (a test hook of the context): 2 to 4,096 distinct keys, every other decision falls to the index.
+    # Sizes reach the single-workgroup sort, the bucket path with in-LDS buckets, the bucket path with
+    # oversized buckets (16 keys -> buckets of 6,500) and the radix passes.  Expected order: the
+    # oracle's sort of the same cut keys.
+    P = Q = 1
+    series = np.zeros((n + P + Q - 1, 1, 1), np.float32)
+    mask = np.uint64(((1 << key_bits) - 1) << (64 - key_bits))
+    with pgti.Context(0) as ctx:
+        ctx.set_sort_test_hooks(key_bits=key_bits)
+        ctx.load_series(series, P, Q, 4, pgti.PGTI_F32, [0.0], [1.0])
+        for seed, epoch in [(0, 0), (12345, 3)]:
+            want = oracle.sort_pairs(oracle.keys(seed, epoch, n) & mask)
+            assert ctx.epoch_indices(seed, epoch) == n
+            got = ctx.get_indices()
+            assert np.array_equal(got, want), (n, key_bits, seed)
+        # one rank's piece of the same order
+        want = oracle.sort_pairs(oracle.keys(5, 1, n) & mask)
+        lo, hi = oracle.rank_share(n, 2, 5)
+        ctx.epoch_indices(5, 1, 2, 5)
+        assert np.array_equal(ctx.get_indices(), want[lo:hi])
+        ctx.set_sort_test_hooks()  # full keys again: the ordinary epoch order
         ctx.epoch_indices(0, 0)
         assert np.array_equal(ctx.get_indices(), oracle.epoch_perm(0, 0, n))
 

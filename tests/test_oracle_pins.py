@@ -327,6 +327,16 @@ def test_key_bits_look_uniform():
         assert 0.45 < frac < 0.55
 
 
+def test_key_list_is_the_scalar_key_and_forced_ties_sort_by_index():
+    ks = oracle.keys(9, 4, 300)
+    assert [int(k) for k in ks] == [oracle.key(9, 4, i) for i in range(300)]
+    # keys cut to their top 3 bits: 8 distinct values, so most of the order is decided by the index;
+    # numpy's stable argsort is that order
+    cut = ks & np.uint64(0xE000000000000000)
+    assert len(set(cut.tolist())) <= 8
+    assert np.array_equal(oracle.sort_pairs(cut), np.argsort(cut, kind="stable").astype(np.int32))
+
+
 @pytest.mark.parametrize("seed,epoch,n", [(0, 0, 1977), (7, 1, 6569), (123, 9, 1), (5, 5, 2)])
 def test_epoch_perm_is_argsort_of_keys(seed, epoch, n):
     perm = oracle.epoch_perm(seed, epoch, n)
