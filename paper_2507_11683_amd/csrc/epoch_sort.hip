@@ -8,8 +8,8 @@
 // Three ways to get that order, by the number of keys n:
 //   n <= 1,024       one launch of one workgroup: keys are generated into LDS and ordered by
 //                    (key, index) with a bitonic network.
-//   n <= 1,048,576   (every benchmark workload) three launches: count the keys per bucket of the top
-//                    4..10 key bits; scatter every (key, index) into its bucket (place inside the
+//   n <= 4,194,304   (every benchmark workload) three launches: count the keys per bucket of the top
+//                    4..12 key bits; scatter every (key, index) into its bucket (place inside the
 //                    bucket arbitrary: LDS and global integer atomics); one workgroup per bucket
 //                    orders its few hundred pairs in LDS, again by (key, index).  The pairs are all
 //                    distinct, so the result does not depend on the order the atomics resolved in.
@@ -255,7 +255,7 @@ __global__ void __launch_bounds__(kSmallSortThreads) small_sort_kernel(uint64_t 
 // ---- bucket path: count, scatter, one workgroup per bucket --------------------------------------
 // Bucket of a key = its top `dbits` bits, D = 2^dbits <= kMaxSortBuckets buckets.  tot[], cursor[] (D
 // entries each) are zero between sorts: the last kernel clears what the first two filled.
-constexpr uint32_t kBucketBins = kMaxSortBuckets / kThreads;  // bins per thread in the offset scan: 4
+constexpr uint32_t kBucketBins = kMaxSortBuckets / kThreads;  // bins per thread in the offset scan: 16
 static_assert(kBucketBins * kThreads == kMaxSortBuckets, "whole bins per thread");
 
 __device__ __forceinline__ uint64_t epoch_key(uint64_t h1, uint64_t counter, uint64_t key_mask) {
@@ -513,7 +513,8 @@ hipError_t launch_expand_batches(const int32_t* order, uint32_t n_full, uint32_t
 namespace pgti {
 namespace {
 
-constexpr uint32_t kStaticSortKeys = kBucketPathKeys;  // 1,048,576 keys: the whole bucket path
+constexpr uint32_t kStaticSortKeys = 1u << 20;  // 1,048,576 keys, ten times the largest dataset of the paper
+static_assert(kStaticSortKeys <= kBucketPathKeys, "the allocation-free call only has a workspace for the bucket path");
 constexpr size_t kStaticKeysBytes = sizeof(uint64_t) * kStaticSortKeys;
 constexpr size_t kStaticValsBytes = sizeof(int32_t) * kStaticSortKeys;
 constexpr size_t kStaticBucketBytes = sizeof(uint32_t) * kSortBucketWords;

@@ -107,9 +107,9 @@ hipError_t launch_reduce_rows(const double* row_acc, int64_t T, int32_t N, int32
 
 // ---- epoch_sort.hip -------------------------------------------------------------------------
 constexpr uint32_t kSortTile = 2048;          // keys per workgroup per pass
-constexpr uint32_t kMaxSortBuckets = 1024;    // bucket path: buckets of the top key bits
+constexpr uint32_t kMaxSortBuckets = 4096;    // bucket path: buckets of the top key bits
 constexpr uint32_t kBucketSortKeys = 2048;    // bucket path: largest bucket ordered in LDS
-constexpr uint32_t kBucketPathKeys = 1u << 20;  // bucket path up to this many keys (average bucket <= 1024)
+constexpr uint32_t kBucketPathKeys = 1u << 22;  // bucket path up to this many keys (average bucket <= 1024)
 // d_bucket: tot[kMaxSortBuckets], cursor[kMaxSortBuckets], off[kMaxSortBuckets + 1]; tot and cursor
 // must be zero when a sort starts (zeroed at allocation, and by the last kernel of every sort).
 constexpr uint32_t kSortBucketWords = 3 * kMaxSortBuckets + 1;

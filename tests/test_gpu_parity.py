@@ -347,10 +347,10 @@ def test_identity_channel_returns_stored_bits():
 # index generation on its own
 # ----------------------------------------------------------------------------------------------
 @pytest.mark.parametrize("n", [1, 2, 3, 63, 64, 65, 700, 1023, 1024, 1025, 1977, 2047, 2048, 2049, 3000, 4095, 4096, 4097, 6144, 10000, 105097, 500000, 524288, 524289,
-                               1048576, 1048577, 1300003])
+                               1048576, 1048577, 1300003, 4194304, 4194305, 4500007])
 def test_epoch_order_sizes(n):
     # n spans one lane, one wave, the single-workgroup path up to 1024 keys (powers of two and ragged
-    # sizes), the bucket path up to 2^20 keys with 16 to 1024 buckets, and the radix passes beyond
+    # sizes), the bucket path up to 2^22 keys with 16 to 4096 buckets, and the radix passes beyond
     # (the per-digit scan over more than 256 tiles runs in several chunks with a carry)
     P = Q = 1
     T = n + P + Q - 1
@@ -395,13 +395,14 @@ def test_epoch_order_with_oversized_buckets():
 
 
 @pytest.mark.parametrize("n,key_bits", [(700, 4), (1024, 1), (1977, 4), (30000, 4), (105097, 4), (105097, 9),
-                                        (1100003, 4), (1100003, 12)])
+                                        (1100003, 12), (4200011, 4), (4200011, 12)])
 def test_equal_keys_are_ordered_by_index(n, key_bits):
     # The full 64-bit keys of distinct starts never collide, so the index half of the (key, index)
     # order is never decisive in an ordinary epoch.  Here the keys are cut to their top few bits
     # (a test hook of the context): 2 to 4,096 distinct keys, every other decision falls to the index.
     # Sizes reach the single-workgroup sort, the bucket path with in-LDS buckets, the bucket path with
-    # oversized buckets (16 keys -> buckets of 6,500) and the radix passes.  Expected order: the
+    # oversized buckets (16 keys -> buckets of 6,500), 4,096 buckets of equal keys, and the radix passes
+    # (beyond 2^22 keys).  Expected order: the
     # oracle's sort of the same cut keys.
     P = Q = 1
     series = np.zeros((n + P + Q - 1, 1, 1), np.float32)
