@@ -232,8 +232,12 @@ class Runner:
             sync()
             times.append(time.perf_counter() - t0)
         t = sorted(times)[len(times) // 2]
+        # bytes that have to move per snapshot: algorithmic for the global shuffle, the unique-bytes ideal of a
+        # full batch (shared source rows read once) for consecutive-start orders
+        moved = self.unique_bytes(1) / min(self.w.B, self.n_share)
         return {"value": snaps / t, "unit": "snapshots/s", "ms": t * 1e3, "epochs": n_epochs, "snapshots": snaps,
-                "gb_per_s": snaps * self.bps / t / 1e9, "pct_of_hbm_peak": snaps * self.bps / t / 1e9 / HBM_PEAK_GBS * 100,
+                "gb_per_s": snaps * moved / t / 1e9, "pct_of_hbm_peak": snaps * moved / t / 1e9 / HBM_PEAK_GBS * 100,
+                "bytes_basis": "algorithmic" if self.order == "shuffle" else "unique-bytes ideal",
                 "batches_per_launch": per_launch, "caller_streams": n_streams, "passes": reps}
 
     def unique_bytes(self, per_launch: int) -> int:
@@ -400,6 +404,7 @@ def main():
     r = Runner(ctx, w, args.order, args.out_dtype, side_stream, args.batches_per_launch, args.out_pairs)
     k, nb = r.k, r.nb
     steps = args.steps or nb * len(w.epochs)
+    moved_per_snapshot = r.unique_bytes(1) / min(w.B, r.n_share)  # = the algorithmic bytes for the global shuffle
 
     # ---- the requested steps in the steady state of a run, k batches per launch ---------------------
     snaps, elapsed = r.steady_steps(steps, args.warmup, k)
@@ -424,13 +429,13 @@ def main():
         snaps2, elapsed2 = r.steady_steps(steps, args.warmup, 1, n_streams=2)
     one_batch = {
         "value": snaps1 / elapsed1, "unit": "snapshots/s", "ms_per_step": elapsed1 / steps * 1e3,
-        "gb_per_s": snaps1 * r.bps / elapsed1 / 1e9,
+        "gb_per_s": snaps1 * moved_per_snapshot / elapsed1 / 1e9,
         "roofline": rate_1,
         "full_epoch_one_stream": r.epochs(n_ep, 1, 1),
         # independent batches alternated over two caller streams: the tail of one launch overlaps the
         # ramp of the next (each stream is ordered behind the share by the library)
         "two_streams": {"value": snaps2 / elapsed2, "unit": "snapshots/s", "ms_per_step": elapsed2 / steps * 1e3,
-                        "gb_per_s": snaps2 * r.bps / elapsed2 / 1e9},
+                        "gb_per_s": snaps2 * moved_per_snapshot / elapsed2 / 1e9},
         "full_epoch_two_streams": r.epochs(n_ep, 1, 2),
     }
 
@@ -465,8 +470,8 @@ def main():
                    "timed_region": "steps are consecutive batches of a run in progress: the epoch's index list is "
                                    "generated once per epoch, inside the timed steps only when they cross an epoch "
                                    "boundary; full_epoch times a whole epoch with it"},
-        "gb_per_s": snaps * r.bps / elapsed / 1e9,
-        "pct_of_hbm_peak": snaps * r.bps / elapsed / 1e9 / HBM_PEAK_GBS * 100,
+        "gb_per_s": snaps * moved_per_snapshot / elapsed / 1e9,
+        "pct_of_hbm_peak": snaps * moved_per_snapshot / elapsed / 1e9 / HBM_PEAK_GBS * 100,
         "roofline": {
             "bound": "hbm", "achieved": rate_k["achieved"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
             "frac": rate_k["frac"], "traffic": traffic, "traffic_source": traffic_source,
