@@ -904,6 +904,47 @@ def test_library_statistics(storage_name):
         _check_batches(ctx, _oracle_series(series, storage), storage, w.P, w.Q, w.B, got_m, got_s, share, [0, 17])
 
 
+STATS_GEOMETRIES = [  # (T, N, F_in, time_of_day_period): quad / pair / scalar accesses, ragged tiles, many features
+    (50, 7, 1, 0), (33, 5, 3, 0), (70, 300, 1, 0), (40, 13, 11, 0), (61, 3, 300, 0), (100, 1000, 2, 0), (65, 129, 4, 0),
+    (97, 640, 2, 0), (45, 514, 1, 24), (37, 511, 1, 7), (53, 33, 2, 288), (29, 9, 299, 5)]
+
+
+@pytest.mark.parametrize("storage_name", ["f32", "bf16"])
+@pytest.mark.parametrize("source", ["host", "device"])
+@pytest.mark.parametrize("geom", STATS_GEOMETRIES, ids=lambda g: "T%d_N%d_F%d_tod%d" % g)
+def test_library_statistics_any_geometry(geom, source, storage_name):
+    # The load's streaming kernel over shapes that reach each of its access modes (16-byte quads, 8-byte
+    # pairs + time of day, single elements), partial tiles in both directions, rows that are not a
+    # multiple of the 32 a workgroup owns, and more than 256 features (several feature groups).  The
+    # per-feature statistics must equal the oracle's sequential sums bit for bit and the resident
+    # series (fp32 or bf16-rounded, time of day appended) must be what the oracle builds.
+    T, N, F_in, period = geom
+    rng = np.random.default_rng(T * 1000 + N)
+    data = (rng.standard_normal((T, N, F_in)) * rng.uniform(1, 30, F_in) + rng.uniform(-50, 80, F_in)).astype(np.float32)
+    full = oracle.add_time_of_day(data, period) if period else data
+    F = full.shape[2]
+    want_m, want_s = oracle.series_stats(full)
+    storage = pgti.PGTI_F32 if storage_name == "f32" else pgti.PGTI_BF16
+    src = data if source == "host" else torch.from_numpy(data).cuda()
+    P, Q, B = 3, 2, 4
+    with pgti.Context(0) as ctx:
+        ctx.load_series_ex(src, P, Q, B, storage, stats_rule=pgti.PGTI_STATS_FEATURE_GLOBAL, time_of_day_period=period)
+        got_m, got_s = ctx.get_stats()
+        assert got_m.shape == (F,)
+        assert np.array_equal(got_m.view(np.uint32), want_m.view(np.uint32)), (got_m[:4], want_m[:4])
+        assert np.array_equal(got_s.view(np.uint32), want_s.view(np.uint32)), (got_s[:4], want_s[:4])
+        ctx.epoch_indices_ex(pgti.PGTI_ORDER_SEQUENTIAL)
+        share = ctx.get_indices()
+        nb = ctx.num_batches()
+        _check_batches(ctx, _oracle_series(full, storage), storage, P, Q, B, got_m, got_s, share, [0, nb // 2, nb - 1])
+        # Algorithm 1's scalar rule on the same data: within one ulp (window-major definition, see the oracle)
+        wm, ws = oracle.alg1_train_stats_fraction(full, P, Q, 0.7)
+        ctx.load_series_ex(src, P, Q, B, storage, stats_rule=pgti.PGTI_STATS_ALG1_TRAIN, train_fraction=0.7,
+                           time_of_day_period=period)
+        gm, gs = ctx.get_stats()
+        assert _ulp_close(gm[0], wm) and _ulp_close(gs[0], ws), (gm[0], wm, gs[0], ws)
+
+
 BF16_OUT_GEOMETRIES = [GEOMETRIES[0], GEOMETRIES[2], GEOMETRIES[4], GEOMETRIES[7], GEOMETRIES[8], GEOMETRIES[9],
                        ROW_GEOMETRIES[0], ROW_GEOMETRIES[2], ROW_GEOMETRIES[5], ROW_GEOMETRIES[6]]
 
