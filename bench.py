@@ -96,7 +96,7 @@ def traffic_from_profiles(workload: str, order: str, out_dtype: str, batches_per
     return None, None
 
 
-def cpu_baseline(w, series, mean, std, n_batches_1core: int, order: int = 0):
+def cpu_baseline(w, series, mean, std, n_batches_1core: int, order: int = 0, seconds: float = 10.0):
     """The oracle as it stands, on this host, on a bounded sample of the same workload."""
     import concurrent.futures as cf
 
@@ -112,7 +112,7 @@ def cpu_baseline(w, series, mean, std, n_batches_1core: int, order: int = 0):
         t0 = time.perf_counter()
         per_batch(1 % nb)
         one = time.perf_counter() - t0
-        n_batches_1core = max(4, min(nb, int(10.0 / max(one, 1e-6))))
+        n_batches_1core = max(4, min(nb, int(seconds / max(one, 1e-6))))
     picks = [int(i * nb / n_batches_1core) for i in range(n_batches_1core)]
     snaps = sum(min(w.B, len(share) - b * w.B) for b in picks)
     t0 = time.perf_counter()
@@ -217,9 +217,10 @@ class Runner:
         sync()
         return n, time.perf_counter() - t0
 
-    def epochs(self, n_epochs: int, per_launch: int, n_streams: int = 1, with_indices: bool = True, reps: int = 3):
+    def epochs(self, n_epochs: int, per_launch: int, n_streams: int = 1, with_indices: bool = True, reps: int = 5):
         """n_epochs whole consecutive epochs; with_indices=False generates the first epoch's order
-        before the clock starts (later epochs of the pass generate theirs inside).  Median of reps."""
+        before the clock starts (later epochs of the pass generate theirs inside).  value / ms: median of
+        reps passes; best_ms: the fastest."""
         sync, times, snaps = self.torch.cuda.synchronize, [], 0
         for _ in range(reps):
             self.enqueue(0, min(self.nb, 2 * per_launch * n_streams), per_launch, n_streams)  # warm both streams
@@ -235,7 +236,8 @@ class Runner:
         # bytes that have to move per snapshot: algorithmic for the global shuffle, the unique-bytes ideal of a
         # full batch (shared source rows read once) for consecutive-start orders
         moved = self.unique_bytes(1) / min(self.w.B, self.n_share)
-        return {"value": snaps / t, "unit": "snapshots/s", "ms": t * 1e3, "epochs": n_epochs, "snapshots": snaps,
+        return {"value": snaps / t, "unit": "snapshots/s", "ms": t * 1e3, "best_ms": min(times) * 1e3,
+                "epochs": n_epochs, "snapshots": snaps,
                 "gb_per_s": snaps * moved / t / 1e9, "pct_of_hbm_peak": snaps * moved / t / 1e9 / HBM_PEAK_GBS * 100,
                 "bytes_basis": "algorithmic" if self.order == "shuffle" else "unique-bytes ideal",
                 "batches_per_launch": per_launch, "caller_streams": n_streams, "passes": reps}
@@ -296,7 +298,7 @@ class Runner:
         self.xs = self.ys = None
 
 
-def other_workload(name: str, host_series, roofline_launches: int, side_stream):
+def other_workload(name: str, host_series, roofline_launches: int, side_stream, with_cpu: bool):
     """One timed pass of another benchmark configuration: its epochs back to back (index generation
     included), the dominant kernel's rate, and pgti_build_batch one call per batch."""
     import numpy as np
@@ -329,6 +331,10 @@ def other_workload(name: str, host_series, roofline_launches: int, side_stream):
         out["unit"] = "snapshots/s"
         r.release()
     torch.cuda.synchronize()
+    if with_cpu:  # the oracle on a short sample of this workload (about 2 s on one core)
+        t0 = time.perf_counter()
+        out["cpu_baseline"] = cpu_baseline(w, series, mean, std, 0, 0, seconds=2.0)
+        out["cpu_baseline"]["wall_s_including_bf16_rounding_of_the_series"] = time.perf_counter() - t0
     return out
 
 
@@ -505,8 +511,8 @@ def main():
             ow = workloads.WORKLOADS[name]
             same_series = (ow.T, ow.N, ow.F, ow.data_seed, ow.gen_flags) == (w.T, w.N, w.F, w.data_seed, w.gen_flags)
             t0 = time.perf_counter()
-            others[name] = other_workload(name, host if same_series else None, min(args.roofline_launches, 2048),
-                                          side_stream)
+            others[name] = other_workload(name, series if same_series else None, min(args.roofline_launches, 2048),
+                                          side_stream, not args.no_cpu_baseline)
             others[name]["wall_s"] = time.perf_counter() - t0
         result["other_workloads"] = others
 

@@ -200,7 +200,7 @@ int load_impl(pgti_ctx* c, const float* src, const pgti_load_spec* spec) {
     if (src_on_device) PGTI_HIP_TRY(hipDeviceSynchronize());
 
     // The new store is built beside the old one and replaces it only when everything has succeeded:
-    // a failed load leaves the context exactly as it was.  `fresh` is released on every early return.
+    // a failed load leaves the context exactly as it was.  The new store is released on every early return.
     pgti_ctx fresh_store;
     pgti_ctx* nx = &fresh_store;
     struct Release {
