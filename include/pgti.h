@@ -116,6 +116,12 @@ int pgti_load_series_device(pgti_ctx* c, const float* device_series, int64_t T, 
  *                                are mixed; the scalar is used for every feature.
  *     Computed statistics are accumulated in fp64 on the device and rounded to fp32 once; they see
  *     the fp32 values (before any bf16 rounding), including the time-of-day feature.
+ *     PGTI_STATS_FEATURE_GLOBAL fixes the order of the additions, so its result is reproducible to
+ *     the bit on any machine: for each feature, every timestep row is summed node by node, the row
+ *     sums are added in time order, mean = sum / (T*N); the squared deviations (v - mean)*(v - mean),
+ *     difference and product each rounded to fp64, are summed the same way, std = sqrt(sum / (T*N)).
+ *     PGTI_STATS_ALG1_TRAIN is evaluated as the window-count-weighted sum of the same row sums; it
+ *     agrees with a literal window-by-window fp64 loop to within one fp32 unit in the last place.
  * Other fields as the arguments of pgti_load_series.  Errors: as pgti_load_series.
  */
 typedef enum {
