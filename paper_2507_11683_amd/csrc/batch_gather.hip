@@ -22,7 +22,7 @@
 //     implies a dividend for which that held, so the result is accepted on that test alone and
 //     everything else (zeros, subnormals, infinities, NaNs, extreme magnitudes) is divided again
 //     with `/`.  6 full-rate VALU operations per element instead of
-//     about 15 issue slots; it matters when the stored type is bf16 (+7 % bandwidth) and is
+//     about 15 issue slots; it matters when the stored type is bf16 (+4 points of the HBM peak) and is
 //     hidden behind memory time for fp32.  tests/fastdiv_model.c checks the identity on the host
 //     for all 2^32 dividends of hard divisors and for random divisors.
 #include <type_traits>
