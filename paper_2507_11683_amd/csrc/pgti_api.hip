@@ -44,8 +44,7 @@ void free_series(pgti_ctx* c) {
     drop(c->d_keys[1]);
     drop(c->d_vals[0]);
     drop(c->d_vals[1]);
-    drop(c->d_hist[0]);
-    drop(c->d_hist[1]);
+    drop(c->d_hist);
     drop(c->d_tot);
     drop(c->d_bucket);
     drop(c->d_share);
@@ -67,8 +66,8 @@ void adopt_store(pgti_ctx* to, pgti_ctx* from) {
     for (int k = 0; k < 2; ++k) {
         take(to->d_keys[k], from->d_keys[k]);
         take(to->d_vals[k], from->d_vals[k]);
-        take(to->d_hist[k], from->d_hist[k]);
     }
+    take(to->d_hist, from->d_hist);
     take(to->d_tot, from->d_tot);
     take(to->d_bucket, from->d_bucket);
     take(to->d_share, from->d_share);
@@ -139,7 +138,7 @@ int check_geometry(int64_t T, int32_t N, int32_t F, int32_t P, int32_t Q, int32_
 }
 
 SortWorkspace workspace_of(const pgti_ctx* c) {
-    return SortWorkspace{{c->d_keys[0], c->d_keys[1]}, {c->d_vals[0], c->d_vals[1]}, {c->d_hist[0], c->d_hist[1]},
+    return SortWorkspace{{c->d_keys[0], c->d_keys[1]}, {c->d_vals[0], c->d_vals[1]}, c->d_hist,
                          c->d_tot, c->d_bucket, c->bucket_sort_cap, c->sort_key_mask};
 }
 
@@ -235,8 +234,7 @@ int load_impl(pgti_ctx* c, const float* src, const pgti_load_spec* spec) {
     if (int rc = alloc(&nx->d_keys[1], sizeof(uint64_t) * n)) return rc;
     if (int rc = alloc(&nx->d_vals[0], sizeof(int32_t) * n)) return rc;
     if (int rc = alloc(&nx->d_vals[1], sizeof(int32_t) * n)) return rc;
-    if (int rc = alloc(&nx->d_hist[0], sizeof(uint32_t) * 256 * nblk)) return rc;
-    if (int rc = alloc(&nx->d_hist[1], sizeof(uint32_t) * 256 * nblk)) return rc;
+    if (int rc = alloc(&nx->d_hist, sizeof(uint32_t) * 256 * nblk)) return rc;
     if (int rc = alloc(&nx->d_tot, sizeof(uint32_t) * 256)) return rc;
     if (int rc = alloc(&nx->d_bucket, sizeof(uint32_t) * kSortBucketWords)) return rc;
     PGTI_HIP_TRY(hipMemsetAsync(nx->d_bucket, 0, sizeof(uint32_t) * kSortBucketWords, ws));

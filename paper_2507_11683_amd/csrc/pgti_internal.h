@@ -54,7 +54,7 @@ struct pgti_ctx {
     hipStream_t work_stream = nullptr;  // owns the sort and the load-time kernels
     uint64_t* d_keys[2] = {nullptr, nullptr};
     int32_t* d_vals[2] = {nullptr, nullptr};
-    uint32_t* d_hist[2] = {nullptr, nullptr};  // per-(digit, tile) counts of this pass / the next (radix path)
+    uint32_t* d_hist = nullptr;                // per-(digit, tile) counts of the current pass (radix path)
     uint32_t* d_tot = nullptr;                 // [256] digit totals of the current pass (radix path)
     uint32_t* d_bucket = nullptr;              // bucket path: totals, cursors, offsets (see kSortBucketWords)
     uint32_t bucket_sort_cap = 0;              // largest bucket that is ordered in LDS
@@ -107,9 +107,9 @@ hipError_t launch_reduce_rows(const double* row_acc, int64_t T, int32_t N, int32
 
 // ---- epoch_sort.hip -------------------------------------------------------------------------
 constexpr uint32_t kSortTile = 2048;          // keys per workgroup per pass
-constexpr uint32_t kMaxSortBuckets = 4096;    // bucket path: buckets of the top key bits
+constexpr uint32_t kMaxSortBuckets = 1024;    // bucket path: buckets of the top key bits
 constexpr uint32_t kBucketSortKeys = 2048;    // bucket path: largest bucket ordered in LDS
-constexpr uint32_t kBucketPathKeys = 1u << 22;  // bucket path up to this many keys (average bucket <= 1024)
+constexpr uint32_t kBucketPathKeys = 1u << 20;  // bucket path up to this many keys; beyond, the radix passes are as fast or faster
 // d_bucket: tot[kMaxSortBuckets], cursor[kMaxSortBuckets], off[kMaxSortBuckets + 1]; tot and cursor
 // must be zero when a sort starts (zeroed at allocation, and by the last kernel of every sort).
 constexpr uint32_t kSortBucketWords = 3 * kMaxSortBuckets + 1;
@@ -128,7 +128,7 @@ struct SortPlan {
 struct SortWorkspace {
     uint64_t* keys[2];
     int32_t* vals[2];
-    uint32_t* hist[2];        // per-(digit, tile) counts of this pass / the next (radix path)
+    uint32_t* hist;           // per-(digit, tile) counts of the current pass (radix path)
     uint32_t* tot;            // [256] digit totals of the current pass (radix path)
     uint32_t* bucket;         // kSortBucketWords words (bucket path)
     uint32_t bucket_sort_cap; // largest bucket that is ordered in LDS

@@ -350,7 +350,7 @@ def test_identity_channel_returns_stored_bits():
                                1048576, 1048577, 1300003, 4194304, 4194305, 4500007])
 def test_epoch_order_sizes(n):
     # n spans one lane, one wave, the single-workgroup path up to 1024 keys (powers of two and ragged
-    # sizes), the bucket path up to 2^22 keys with 16 to 4096 buckets, and the radix passes beyond
+    # sizes), the bucket path up to 2^20 keys with 16 to 1024 buckets, and the radix passes beyond
     # (the per-digit scan over more than 256 tiles runs in several chunks with a carry)
     P = Q = 1
     T = n + P + Q - 1
@@ -401,8 +401,8 @@ def test_equal_keys_are_ordered_by_index(n, key_bits):
     # order is never decisive in an ordinary epoch.  Here the keys are cut to their top few bits
     # (a test hook of the context): 2 to 4,096 distinct keys, every other decision falls to the index.
     # Sizes reach the single-workgroup sort, the bucket path with in-LDS buckets, the bucket path with
-    # oversized buckets (16 keys -> buckets of 6,500), 4,096 buckets of equal keys, and the radix passes
-    # (beyond 2^22 keys).  Expected order: the
+    # oversized buckets (16 keys -> buckets of 6,500) and the radix passes (beyond 2^20 keys).
+    # Expected order: the
     # oracle's sort of the same cut keys.
     P = Q = 1
     series = np.zeros((n + P + Q - 1, 1, 1), np.float32)
