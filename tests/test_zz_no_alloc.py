@@ -65,6 +65,35 @@ def test_static_epoch_order_back_to_back_on_one_stream_without_host_sync():
     assert np.array_equal(b.cpu().numpy(), oracle.epoch_indices(11, 5, 0, 1, 34249))
 
 
+def test_static_epoch_order_can_be_captured_and_replayed():
+    # the call enqueues kernels only (no allocation, no memset node), so it can sit in a HIP graph;
+    # every replay, with eager work and synchronisations in between, must give the same share
+    n, seed, epoch = 34249, 21, 2
+    want = oracle.epoch_indices(seed, epoch, 1, 3, n)
+    out = torch.empty(len(want) + 8, dtype=torch.int32, device="cuda")
+    s = torch.cuda.Stream()
+    with pgti.Context(0):  # resolves the scratch address on this device before any capture
+        pass
+    with torch.cuda.stream(s):
+        assert pgti.epoch_indices_static(n, seed, epoch, 1, 3, out, s) == len(want)  # eager once
+    s.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g, stream=s):
+        got = pgti.epoch_indices_static(n, seed, epoch, 1, 3, out, torch.cuda.current_stream())
+    assert got == len(want)
+    for rep in range(4):
+        out.fill_(-5)
+        other = pgti.epoch_indices_static(1977, 1, rep, 0, 1, torch.empty(1977, dtype=torch.int32, device="cuda"))  # dirties the scratch
+        torch.cuda.synchronize()
+        assert other == 1977
+        with torch.cuda.stream(s):
+            g.replay()
+        s.synchronize()
+        res = out.cpu().numpy()
+        assert np.array_equal(res[:len(want)], want), rep
+        assert np.all(res[len(want):] == -5)
+
+
 def test_static_epoch_order_rejects_what_it_cannot_hold():
     out = torch.empty(16, dtype=torch.int32, device="cuda")
     lib = pgti.load_library()
