@@ -299,6 +299,80 @@ def test_geometry_sweep(geom, storage_name):
             _check_batches(ctx, ser_o, storage, P, Q, B, mean, std, share, range(ctx.num_batches()))
 
 
+def _bf16_bits_equal(got: np.ndarray, want: np.ndarray) -> bool:
+    same = got == want
+    nan_g = ((got & 0x7F80) == 0x7F80) & ((got & 0x7F) != 0)
+    nan_w = ((want & 0x7F80) == 0x7F80) & ((want & 0x7F) != 0)
+    return bool(np.all(same | (nan_g & nan_w)))
+
+
+def _random_cases(count, seed):
+    rng = np.random.default_rng(seed)
+    cases = []
+    for _ in range(count):
+        F = int(rng.choice([1, 1, 2, 2, 2, 3, 4, 5, 8, 9]))
+        N = int(rng.integers(1, 700))
+        P, Q = int(rng.integers(1, 14)), int(rng.integers(1, 14))
+        B = int(rng.integers(1, 40))
+        T = P + Q - 1 + int(rng.integers(1, 90))
+        cases.append((T, N, F, P, Q, B, int(rng.integers(0, 3)), int(rng.integers(0, 2)), int(rng.integers(0, 2)),
+                      int(rng.integers(0, 2 ** 31))))
+    return cases
+
+
+@pytest.mark.parametrize("case", _random_cases(240, 20250711),
+                         ids=lambda c: "T%d_N%d_F%d_P%d_Q%d_B%d_order%d_store%d_out%d_s%d" % c)
+def test_random_geometries(case):
+    # Seeded random shapes, orders (shuffle / sequential / batch-level shuffle), storage types and
+    # output types; k batches per launch with k drawn per case; special values in the data.  Every
+    # batch of one rank's share against the oracle, bit for bit.
+    T, N, F, P, Q, B, order, store_bf16, out_bf16, seed = case
+    rng = np.random.default_rng(seed)
+    series = _special_series(rng, T, N, F)
+    mean = rng.normal(40, 10, F).astype(np.float32)
+    std = (rng.uniform(0.3, 25, F) * rng.choice([-1.0, 1.0], F)).astype(np.float32)
+    storage = pgti.PGTI_BF16 if store_bf16 else pgti.PGTI_F32
+    n = T - P - Q + 1
+    world = int(rng.integers(1, 4))
+    rank = int(rng.integers(0, world))
+    first = int(rng.integers(0, n))
+    count = int(rng.integers(0, n - first + 1))
+    with pgti.Context(0) as ctx:
+        ctx.load_series(series, P, Q, B, storage, mean, std)
+        ser_o = _oracle_series(series, storage)
+        n_share = ctx.epoch_indices_ex(order, seed=seed, epoch=seed % 7, rank=rank, world=world, first_start=first,
+                                       n_starts=count)
+        share = ctx.get_indices()
+        want = oracle.epoch_indices_ex(order, n, first, count, B, seed, seed % 7, rank, world)
+        assert n_share == len(want) and np.array_equal(share, want)
+        if n_share == 0:
+            return
+        nb = ctx.num_batches()
+        k = int(rng.integers(1, nb + 1))
+        odt = torch.bfloat16 if out_bf16 else torch.float32
+        x = torch.zeros((k, B, P, N, F), dtype=odt, device="cuda")
+        y = torch.zeros((k, B, Q, N, F), dtype=odt, device="cuda")
+        build = ctx.build_batches_bf16 if out_bf16 else ctx.build_batches
+        oracle_build = oracle.build_batch_bf16_out if out_bf16 else oracle.build_batch
+        view = (lambda t: t.view(torch.int16).cpu().numpy().view(np.uint16)) if out_bf16 else (lambda t: t.cpu().numpy())
+        for b0 in range(0, nb, k):
+            kk = min(k, nb - b0)
+            x.zero_()
+            y.zero_()
+            total = build(b0, kk, x, y)
+            torch.cuda.synchronize()
+            starts = want[b0 * B:(b0 + kk) * B]
+            assert total == len(starts)
+            wx, wy = oracle_build(ser_o, storage, P, Q, mean, std, starts)
+            gx = view(x).reshape(k * B, P, N, F)
+            gy = view(y).reshape(k * B, Q, N, F)
+            if out_bf16:
+                assert _bf16_bits_equal(gx[:total], wx) and _bf16_bits_equal(gy[:total], wy), (b0, kk)
+            else:
+                assert _bits_equal(gx[:total], wx) and _bits_equal(gy[:total], wy), (b0, kk)
+            assert not gx[total:].any() and not gy[total:].any()  # nothing written past the valid samples
+
+
 @pytest.mark.parametrize("std", [(8.9, 1.0), (1.9999999, 0.33333334), (-7.25, 1.0000001),
                                  (1e-12, 3e10), (2.3283064e-10, 4294967040.0), (1e-30, 1e30)])
 @pytest.mark.parametrize("storage_name", ["f32", "bf16"])
